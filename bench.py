@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the subsampled-global-attention hot path on one MI355X.
+
+One "step" = one layer's pass of the whole path on resident inputs:
+``agg_kv_subsample`` (index list, grid gather, mean terms) followed by
+``agg_global_attn_fwd``.  The dense s = 1 baseline (``agg_dense_global_attn_fwd``)
+is timed beside it, not inside the step.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload f100|f300|f333|f800|tiny]
+                  [--also f300,f800] [--no-dense] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "ms/layer & TFLOP/s (frac of bf16 peak) for subsampled global attn, 100/300/800 frames"
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz)
+PEAK_HBM_GBS = 8000.0
+
+
+def sga_flops(NQ, M, H, D):
+    # QK^T and PV, 2 flops per multiply-add, all heads; +2 columns for the self and mean terms
+    return 4.0 * NQ * (M + 2) * D * H
+
+
+def time_events(fn, steps, warmup):
+    """Average milliseconds of fn() over `steps` launches, HIP events on torch's current
+    stream (the stream every library call here is enqueued on)."""
+    import torch
+
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    stop = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    for i in range(steps):
+        start[i].record()
+        fn()
+        stop[i].record()
+    torch.cuda.synchronize()
+    ms = [a.elapsed_time(b) for a, b in zip(start, stop)]
+    return sum(ms) / len(ms), min(ms)
+
+
+def run_workload(name, steps, warmup, dense, log):
+    import torch
+
+    from paper_2512_02541_amd import binding as agg
+    from paper_2512_02541_amd import harness, inputs
+
+    w = inputs.WORKLOADS[name]
+    shape = harness.shape_of(w)
+    log("generating %s (%d frames, %d tokens)" % (name, w.N, w.NQ))
+    q, k, v = inputs.make_qkv(w, "cuda")
+    buf = harness.alloc(shape, "cuda")
+    torch.cuda.synchronize()
+
+    def step():
+        harness.subsample(buf, k, v)
+        harness.attend(buf, q, k, v)
+
+    # whole step: wall clock bracketed by synchronize, exactly `steps` passes
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_gather, _ = time_events(lambda: harness.subsample(buf, k, v), steps, 1)
+    ms_attn, ms_attn_min = time_events(lambda: harness.attend(buf, q, k, v), steps, 1)
+
+    flops = sga_flops(w.NQ, buf.M, w.H, w.D)
+    C = w.H * w.D
+    gather_bytes = 2.0 * w.NQ * C * 2 + 2.0 * buf.M * C * 2  # K,V read once; kept rows written once
+    res = {
+        "workload": name, "frames": w.N, "NQ": w.NQ, "M": buf.M, "n_dropped": buf.n_dropped,
+        "strides": [w.s_h, w.s_w],
+        "ms_layer": ms_step, "ms_gather": ms_gather, "ms_attn": ms_attn, "ms_attn_min": ms_attn_min,
+        "tflops_layer": flops / (ms_step * 1e-3) / 1e12,
+        "tflops_attn": flops / (ms_attn * 1e-3) / 1e12,
+        "frac_peak_attn": flops / (ms_attn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "gather_gbs": gather_bytes / (ms_gather * 1e-3) / 1e9,
+        "gather_frac_hbm": gather_bytes / (ms_gather * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "flops_per_layer": flops, "gather_bytes": gather_bytes,
+    }
+    if dense:
+        nws = agg.agg_dense_workspace_bytes(shape)
+        ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+        Od = torch.empty_like(buf.O)
+
+        def dense_step():
+            agg.agg_dense_global_attn_fwd(shape, q, k, v, Od, None, ws, nws)
+
+        ms_dense, _ = time_events(dense_step, max(1, min(steps, 3)), 1)
+        dflops = 4.0 * w.NQ * w.NQ * w.D * w.H
+        res.update({"ms_dense": ms_dense, "tflops_dense": dflops / (ms_dense * 1e-3) / 1e12,
+                    "speedup_vs_dense": ms_dense / ms_step,
+                    "ideal_speedup": w.NQ / buf.M})
+        del ws, Od
+    return res, (w, shape, q, k, v, buf)
+
+
+def cpu_baseline(w, shape, q, k, v, buf, flops, nrows, log):
+    """The oracle, as it stands, on the host's cores: gather + mean in full, attention on
+    `nrows` evenly spaced query rows; also used to re-check the GPU output."""
+    import numpy as np
+
+    from oracle import sga_oracle as orc
+    from paper_2512_02541_amd import inputs
+
+    o = orc.Shape(shape.B, shape.N, shape.n_h, shape.n_w, shape.n_special, shape.H, shape.D,
+                  shape.s_h, shape.s_w, shape.keep_first_frame, shape.flags, shape.scale,
+                  shape.mean_logit_bias)
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    log("oracle: gather + mean in full")
+    t0 = time.perf_counter()
+    idx = orc.kept_indices(o)
+    M, nd = orc.counts(o)
+    Kc, Vc = orc.gather(o, kb, vb, idx)
+    km, vm = orc.mean(o, kb, vb)
+    t_pre = time.perf_counter() - t0
+    rows = np.unique(np.linspace(0, shape.NQ - 1, nrows).astype(np.int64))
+    log("oracle: attention on %d sampled rows" % len(rows))
+    t0 = time.perf_counter()
+    want, _, _ = orc.attn_rows(o, qb, kb, vb, Kc, Vc, km, vm, nd, rows)
+    t_rows = time.perf_counter() - t0
+    t_full = t_pre + t_rows * shape.NQ / len(rows)
+    got = buf.O[:, rows].float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - want)
+    base = {
+        "value": flops / t_full / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(),
+        "kind": "oracle",
+        "sample": "gather+mean in full (%.2f s); attention on %d of %d query rows x %d heads "
+                  "against the full compacted set (%.2f s), extrapolated linearly to all rows "
+                  "(%.0f s per layer)" % (t_pre, len(rows), shape.NQ, shape.H, t_rows, t_full),
+        "rows_per_s": len(rows) / t_rows, "extrapolated_s_per_layer": t_full,
+    }
+    parity = {"rows": int(len(rows)), "max_abs": float(err.max()), "mean_abs": float(err.mean())}
+    return base, parity
+
+
+def read_traffic(name):
+    """HBM bytes per attention launch from the committed rocprofv3 counter summary, if any."""
+    path = os.path.join(ROOT, "profiles", "sga_attn_%s_pmc.txt" % name)
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="f100")
+    ap.add_argument("--also", default="f300,f800",
+                    help="comma list of further workloads timed (SGA only) into config.also")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=384)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    def log(msg):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    from paper_2512_02541_amd import binding as agg
+
+    agg.lib()  # fail loudly if the HIP library is missing
+
+    res, ctx = run_workload(args.workload, args.steps, args.warmup, not args.no_dense, log)
+    cpu, parity = (None, None)
+    if not args.no_cpu:
+        cpu, parity = cpu_baseline(*ctx, res["flops_per_layer"], args.cpu_rows, log)
+    del ctx
+    torch.cuda.empty_cache()
+
+    also = []
+    for name in [x for x in args.also.split(",") if x and x != args.workload]:
+        r, c = run_workload(name, max(2, args.steps // 3), 1, False, log)
+        del c
+        torch.cuda.empty_cache()
+        also.append({k: r[k] for k in ("workload", "frames", "NQ", "M", "strides", "ms_layer",
+                                       "ms_gather", "ms_attn", "tflops_attn", "frac_peak_attn",
+                                       "gather_gbs")})
+
+    out = {
+        "metric": METRIC,
+        "value": res["tflops_layer"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_layer"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %d frames x (37x37+5) tokens, 16 heads x 64, strides (%d,%d), "
+                               "diag+mean, first frame kept" % (res["workload"], res["frames"],
+                                                                res["strides"][0], res["strides"][1])
+                   if res["workload"] != "tiny" else "tiny",
+                   "NQ": res["NQ"], "M": res["M"], "n_dropped": res["n_dropped"],
+                   "ms_gather": res["ms_gather"], "ms_attn": res["ms_attn"],
+                   "gather_gbs": res["gather_gbs"], "gather_frac_hbm": res["gather_frac_hbm"],
+                   "frac_bf16_peak_layer": res["tflops_layer"] / PEAK_BF16_TFLOPS,
+                   "ms_dense": res.get("ms_dense"), "tflops_dense": res.get("tflops_dense"),
+                   "speedup_vs_dense": res.get("speedup_vs_dense"),
+                   "ideal_speedup": res.get("ideal_speedup"),
+                   "paper_context": "end-to-end speedups ~2x/4-5x/8-10x at 100/300/800 frames on "
+                                    "A100-80GB with FlashAttention-2 (whole model, not this layer)",
+                   "also": also, "parity_vs_oracle": parity},
+        "roofline": {"bound": "mfma", "achieved": res["tflops_attn"], "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": res["frac_peak_attn"],
+                     "traffic": read_traffic(res["workload"]),
+                     "kernel": "sga_attn_kernel", "ms": res["ms_attn"]},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

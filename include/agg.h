@@ -1,0 +1,148 @@
+/*
+ * agg -- subsampled global attention (SGA) for VGGT-style models on AMD MI355X (gfx950).
+ *
+ * C ABI of libagg.so.  The operation is the one the AVGGT paper defines in its
+ * Sec. 4.3 ("Subsampling Global Attention") on the token layout of its Sec. 4.1:
+ * a sequence is N frames of L = n_special + n_h*n_w tokens; every token is a
+ * query; keys/values are all special tokens, all of frame 0 when the reference
+ * frame is kept whole, and on every other patch grid the first token of each
+ * s_h x s_w window; a query whose own token was dropped also sees its own
+ * key/value ("diagonal preservation"); all dropped patches are represented by
+ * one mean key/value pair; the three parts share one softmax.
+ *
+ * Conventions
+ *   - Token id inside a sequence: i = f*L + t.  t < n_special is a special token,
+ *     otherwise patch p = t - n_special at grid row p / n_w, column p % n_w.
+ *   - Q, K, V, O: bf16, device memory, contiguous [B, N*L, H, D] (token-major:
+ *     what a fused QKV projection writes and an output projection reads).
+ *   - D must be 64.  Pointers to bf16 tensors must be 16-byte aligned.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Every call only enqueues work on that stream: no allocation, no
+ *     synchronisation, no retained pointers.  The caller owns every buffer.
+ *   - Return value: AGG_OK or a negative agg_status.  All argument validation
+ *     happens before the first launch, so every error except AGG_ERR_LAUNCH is
+ *     reported without touching the GPU.  Faults inside a kernel surface at the
+ *     caller's next synchronisation, as with any HIP launch.
+ *
+ * Compacted key/value format ("fragment order")
+ *   Kc and Vc hold, per (batch, head), the M kept rows padded with zero rows to
+ *   M_pad = 64*ceil(M/64), as consecutive 64-row tiles of 4096 bf16 (8 KiB).
+ *   Inside a tile the elements are permuted so that a linear copy into LDS lets
+ *   every wavefront lane fetch its MFMA operand as one 16-byte read:
+ *     Kc: row m, channel d  ->  tile m/64, then with km = m%64
+ *         ((( (km/32)*4 + d/16 )*2 + (d%16)/8 )*32 + km%32)*8 + d%8
+ *     Vc: row m, channel d  ->  tile m/64, then with km = m%64, u = km%16
+ *         ((( km/16 )*2 + (u%8)/4 )*64 + d)*8 + (u/8)*4 + u%4
+ *   agg_kc_offset()/agg_vc_offset() evaluate these on the host.  Row m of the
+ *   compacted set is token idx[m]; idx is ascending.
+ */
+#ifndef AGG_H_
+#define AGG_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct agg_shape {
+  int32_t B, N;             /* batch size, frames                       (Sec. 4.1) */
+  int32_t n_h, n_w;         /* patch grid                               (Sec. 4.1) */
+  int32_t n_special;        /* special tokens per frame, stored before the patches */
+  int32_t H, D;             /* heads, head dimension (D = 64)                      */
+  int32_t s_h, s_w;         /* window strides; (1,1) = no subsampling   (Sec. 4.3) */
+  int32_t keep_first_frame; /* 1: frame 0 kept whole (VGGT); 0: all frames (pi^3)  */
+  uint32_t flags;           /* AGG_DIAG | AGG_MEAN                      (Sec. 4.3) */
+  float scale;              /* softmax scale, 1/sqrt(D)                            */
+  float mean_logit_bias;    /* added to the mean column's logit; 0 = one plain column */
+} agg_shape;
+
+enum { AGG_DIAG = 1u, AGG_MEAN = 2u };
+
+typedef enum agg_status {
+  AGG_OK = 0,
+  AGG_ERR_NULL = -1,        /* a required pointer is NULL                          */
+  AGG_ERR_SHAPE = -2,       /* a dimension or stride is < 1, or flags unknown      */
+  AGG_ERR_UNSUPPORTED = -3, /* D != 64                                             */
+  AGG_ERR_ALIGN = -4,       /* a tensor pointer is not 16-byte aligned             */
+  AGG_ERR_WORKSPACE = -5,   /* workspace smaller than the matching *_workspace_bytes */
+  AGG_ERR_OVERFLOW = -6,    /* N*L, M_pad or a tensor's element count exceeds the index range */
+  AGG_ERR_LAUNCH = -7       /* hipGetLastError() after a launch was not hipSuccess */
+} agg_status;
+
+const char* agg_status_string(int status);
+
+/* Sec. 4.3 table: sigma in {2,4,6,9} -> (s_h, s_w) = (1,2),(2,2),(2,3),(3,3); sigma 1 -> (1,1).
+ * Any other sigma: AGG_ERR_SHAPE. */
+int agg_sigma_to_strides(int sigma, int32_t* s_h, int32_t* s_w);
+
+/* Host only.  M = number of kept key/value rows per sequence,
+ * n_dropped = number of patch tokens left out (Sec. 4.3).  Either output may be NULL. */
+int agg_kv_count(const agg_shape* shape, int64_t* M, int64_t* n_dropped);
+
+/* Host only.  Writes the ascending token ids of the kept set into idx[M] (host memory). */
+int agg_kv_indices_host(const agg_shape* shape, int32_t* idx);
+
+/* Host only.  Writes the ascending token ids of the dropped patches (the set the mean
+ * component averages, Sec. 4.3) into idx[n_dropped] (host memory). */
+int agg_dropped_indices_host(const agg_shape* shape, int32_t* idx);
+
+/* Host only.  Size of ONE compacted tensor (Kc or Vc) in bytes, B*H*M_pad*D*2, and M_pad. */
+int agg_kv_compact_bytes(const agg_shape* shape, size_t* bytes, int64_t* M_pad);
+
+/* Host only.  Element offsets inside one (batch, head) block of Kc / Vc (see above). */
+int64_t agg_kc_offset(int64_t m, int32_t d);
+int64_t agg_vc_offset(int64_t m, int32_t d);
+
+/* Host only.  Scratch bytes agg_kv_subsample needs (partial sums of the mean). */
+size_t agg_workspace_bytes(const agg_shape* shape);
+
+/* Host only.  Scratch bytes agg_dense_global_attn_fwd needs (K and V in fragment order). */
+size_t agg_dense_workspace_bytes(const agg_shape* shape);
+
+/*
+ * Sec. 4.3, subsampling + mean component.  Builds on the device:
+ *   idx   [M] int32        ascending kept token ids (same for every batch element/head/layer)
+ *   Kc,Vc bf16, agg_kv_compact_bytes() each, fragment order, zero padded
+ *   kmean,vmean [B,H,D] float32: mean of K resp. V over all dropped patch tokens of the
+ *         sequence (zeros when nothing is dropped).  Accumulated in a fixed order:
+ *         results are bit-reproducible run to run.
+ * K, V: device bf16 [B, N*L, H, D].  workspace: device, >= agg_workspace_bytes().
+ * idx may be NULL (not written).  kmean/vmean must be non-NULL.
+ */
+int agg_kv_subsample(const agg_shape* shape, const void* K, const void* V, void* Kc, void* Vc,
+                     int32_t* idx, float* kmean, float* vmean, void* workspace,
+                     size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Sec. 4.3, the attention itself.  For every query i of every (batch, head):
+ *   softmax over { scale*<q_i, Kc[m]> : m < M }
+ *                u { scale*<q_i, k_i> }                    if AGG_DIAG and token i was dropped
+ *                u { scale*<q_i, kmean> + mean_logit_bias } if AGG_MEAN and n_dropped > 0
+ *   O[i] = sum of the probabilities times the matching value rows (Vc[m], v_i, vmean).
+ * Q, K, V: device bf16 [B, N*L, H, D] (K, V are read only for the self terms).
+ * Kc, Vc, kmean, vmean: as written by agg_kv_subsample for the same shape.
+ * O: device bf16 [B, N*L, H, D].  lse: device float32 [B, H, N*L] (natural-log
+ * log-sum-exp of each row's logits) or NULL.
+ * With s_h = s_w = 1 nothing is dropped and the result is ordinary global attention.
+ */
+int agg_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V,
+                        const void* Kc, const void* Vc, const float* kmean, const float* vmean,
+                        void* O, float* lse, void* hip_stream);
+
+/*
+ * Sec. 4.2: ordinary global attention over the (B, N*L, C) layout -- every token of the
+ * sequence is a key -- the s = 1 baseline SGA is measured against.  shape->s_h, s_w,
+ * flags and keep_first_frame are ignored.  workspace: device, >= agg_dense_workspace_bytes();
+ * it receives K and V repacked into fragment order and can be discarded after the call's
+ * work has finished.
+ */
+int agg_dense_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V,
+                              void* O, float* lse, void* workspace, size_t workspace_bytes,
+                              void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGG_H_ */

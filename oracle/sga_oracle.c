@@ -157,6 +157,7 @@ void osga_mean(const osga_shape* s, const uint16_t* K, const uint16_t* V, double
                double* vmean) {
   int64_t NQ = (int64_t)s->N * tokens_per_frame(s);
   int64_t H = s->H, D = s->D;
+#pragma omp parallel for collapse(2) schedule(static)
   for (int64_t b = 0; b < s->B; ++b)
     for (int64_t h = 0; h < H; ++h) {
       double* km = kmean + (b * H + h) * D;

@@ -1,0 +1,200 @@
+"""ctypes binding of libagg.so: same names as the C ABI in ``include/agg.h``.
+
+Argument marshalling only -- every step of the path runs in the library's HIP
+kernels.  PyTorch supplies device memory (``tensor.data_ptr()``) and the HIP
+stream.  A missing library is an error: there is no fallback implementation.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libagg.so")
+
+AGG_DIAG = 1
+AGG_MEAN = 2
+AGG_OK = 0
+
+
+class AggError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+class agg_shape(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("N", ctypes.c_int32),
+        ("n_h", ctypes.c_int32), ("n_w", ctypes.c_int32),
+        ("n_special", ctypes.c_int32),
+        ("H", ctypes.c_int32), ("D", ctypes.c_int32),
+        ("s_h", ctypes.c_int32), ("s_w", ctypes.c_int32),
+        ("keep_first_frame", ctypes.c_int32),
+        ("flags", ctypes.c_uint32),
+        ("scale", ctypes.c_float),
+        ("mean_logit_bias", ctypes.c_float),
+    ]
+
+    @property
+    def L(self) -> int:
+        return self.n_special + self.n_h * self.n_w
+
+    @property
+    def NQ(self) -> int:
+        return self.N * self.L
+
+
+def make_shape(B, N, n_h, n_w, n_special, H, D, s_h, s_w, keep_first_frame=1,
+               flags=AGG_DIAG | AGG_MEAN, scale=None, mean_logit_bias=0.0) -> agg_shape:
+    if scale is None:
+        scale = 1.0 / (D ** 0.5)
+    return agg_shape(B, N, n_h, n_w, n_special, H, D, s_h, s_w, keep_first_frame, flags, scale,
+                     mean_logit_bias)
+
+
+_lib = None
+
+EXPORTS = [
+    "agg_status_string", "agg_sigma_to_strides", "agg_kv_count", "agg_kv_indices_host",
+    "agg_dropped_indices_host", "agg_kv_compact_bytes", "agg_kc_offset", "agg_vc_offset", "agg_workspace_bytes",
+    "agg_dense_workspace_bytes", "agg_kv_subsample", "agg_global_attn_fwd",
+    "agg_dense_global_attn_fwd",
+]
+
+
+def lib():
+    """Opens libagg.so on first use; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "libagg.so is missing at %s -- build it with `python -m paper_2512_02541_amd.build`; "
+            "there is no fallback path" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32p, i64p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+    shp = ctypes.POINTER(agg_shape)
+    L.agg_status_string.restype = ctypes.c_char_p
+    L.agg_status_string.argtypes = [ctypes.c_int]
+    L.agg_sigma_to_strides.argtypes = [ctypes.c_int, i32p, i32p]
+    L.agg_kv_count.argtypes = [shp, i64p, i64p]
+    L.agg_kv_indices_host.argtypes = [shp, vp]
+    L.agg_dropped_indices_host.argtypes = [shp, vp]
+    L.agg_kv_compact_bytes.argtypes = [shp, ctypes.POINTER(ctypes.c_size_t), i64p]
+    L.agg_kc_offset.restype = ctypes.c_int64
+    L.agg_kc_offset.argtypes = [ctypes.c_int64, ctypes.c_int32]
+    L.agg_vc_offset.restype = ctypes.c_int64
+    L.agg_vc_offset.argtypes = [ctypes.c_int64, ctypes.c_int32]
+    L.agg_workspace_bytes.restype = ctypes.c_size_t
+    L.agg_workspace_bytes.argtypes = [shp]
+    L.agg_dense_workspace_bytes.restype = ctypes.c_size_t
+    L.agg_dense_workspace_bytes.argtypes = [shp]
+    L.agg_kv_subsample.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.agg_global_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.agg_dense_global_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str):
+    if status != AGG_OK:
+        raise AggError(status, where)
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / raw int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    if hasattr(t, "data_ptr"):
+        return ctypes.c_void_p(t.data_ptr())
+    return ctypes.c_void_p(t.ctypes.data)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+
+        stream = torch.cuda.current_stream().cuda_stream
+    return ctypes.c_void_p(int(stream))
+
+
+def status_string(status: int) -> str:
+    return lib().agg_status_string(int(status)).decode()
+
+
+def agg_sigma_to_strides(sigma: int):
+    sh, sw = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().agg_sigma_to_strides(int(sigma), ctypes.byref(sh), ctypes.byref(sw)),
+           "agg_sigma_to_strides")
+    return sh.value, sw.value
+
+
+def agg_kv_count(shape: agg_shape):
+    m, nd = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().agg_kv_count(ctypes.byref(shape), ctypes.byref(m), ctypes.byref(nd)),
+           "agg_kv_count")
+    return m.value, nd.value
+
+
+def agg_kv_indices_host(shape: agg_shape):
+    import numpy as np
+
+    m, _ = agg_kv_count(shape)
+    idx = np.empty(m, dtype=np.int32)
+    _check(lib().agg_kv_indices_host(ctypes.byref(shape), _ptr(idx)), "agg_kv_indices_host")
+    return idx
+
+
+def agg_dropped_indices_host(shape: agg_shape):
+    import numpy as np
+
+    _, nd = agg_kv_count(shape)
+    idx = np.empty(nd, dtype=np.int32)
+    _check(lib().agg_dropped_indices_host(ctypes.byref(shape), _ptr(idx)),
+           "agg_dropped_indices_host")
+    return idx
+
+
+def agg_kv_compact_bytes(shape: agg_shape):
+    nbytes, m_pad = ctypes.c_size_t(0), ctypes.c_int64(0)
+    _check(lib().agg_kv_compact_bytes(ctypes.byref(shape), ctypes.byref(nbytes),
+                                      ctypes.byref(m_pad)), "agg_kv_compact_bytes")
+    return nbytes.value, m_pad.value
+
+
+def agg_kc_offset(m: int, d: int) -> int:
+    return int(lib().agg_kc_offset(int(m), int(d)))
+
+
+def agg_vc_offset(m: int, d: int) -> int:
+    return int(lib().agg_vc_offset(int(m), int(d)))
+
+
+def agg_workspace_bytes(shape: agg_shape) -> int:
+    return int(lib().agg_workspace_bytes(ctypes.byref(shape)))
+
+
+def agg_dense_workspace_bytes(shape: agg_shape) -> int:
+    return int(lib().agg_dense_workspace_bytes(ctypes.byref(shape)))
+
+
+def agg_kv_subsample(shape, K, V, Kc, Vc, idx, kmean, vmean, workspace, workspace_bytes,
+                     stream=None):
+    _check(lib().agg_kv_subsample(ctypes.byref(shape), _ptr(K), _ptr(V), _ptr(Kc), _ptr(Vc),
+                                  _ptr(idx), _ptr(kmean), _ptr(vmean), _ptr(workspace),
+                                  int(workspace_bytes), _stream(stream)), "agg_kv_subsample")
+
+
+def agg_global_attn_fwd(shape, Q, K, V, Kc, Vc, kmean, vmean, O, lse=None, stream=None):
+    _check(lib().agg_global_attn_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Kc),
+                                     _ptr(Vc), _ptr(kmean), _ptr(vmean), _ptr(O), _ptr(lse),
+                                     _stream(stream)), "agg_global_attn_fwd")
+
+
+def agg_dense_global_attn_fwd(shape, Q, K, V, O, lse, workspace, workspace_bytes, stream=None):
+    _check(lib().agg_dense_global_attn_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
+                                           _ptr(lse), _ptr(workspace), int(workspace_bytes),
+                                           _stream(stream)), "agg_dense_global_attn_fwd")

@@ -1,0 +1,208 @@
+// Host side of libagg: argument validation, geometry, counts, index list and
+// the extern "C" entry points declared in agg.h.  Nothing here allocates device
+// memory or synchronises; every check runs before the first launch.
+#include <limits.h>
+#include <string.h>
+
+#include "agg_internal.h"
+
+namespace agg {
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Fills Geom from the caller's shape.  `dense` ignores the subsampling fields
+// and treats every token as kept (Sec. 4.2: plain global attention).
+int make_geom(const agg_shape* s, Geom* g, bool dense) {
+  if (!s || !g) return AGG_ERR_NULL;
+  if (s->B < 1 || s->N < 1 || s->n_h < 1 || s->n_w < 1 || s->n_special < 0 || s->H < 1 ||
+      s->D < 1)
+    return AGG_ERR_SHAPE;
+  if (!dense) {
+    if (s->s_h < 1 || s->s_w < 1) return AGG_ERR_SHAPE;
+    if (s->flags & ~(uint32_t)(AGG_DIAG | AGG_MEAN)) return AGG_ERR_SHAPE;
+    if (s->keep_first_frame != 0 && s->keep_first_frame != 1) return AGG_ERR_SHAPE;
+  }
+  if (!(s->scale > 0.0f) || !(s->scale < 1e30f)) return AGG_ERR_SHAPE;
+  if (!(s->mean_logit_bias > -1e30f && s->mean_logit_bias < 1e30f)) return AGG_ERR_SHAPE;
+  if (s->D != kHeadDim) return AGG_ERR_UNSUPPORTED;
+
+  int64_t T = (int64_t)s->n_h * s->n_w;
+  int64_t L = T + s->n_special;
+  if (L > INT32_MAX) return AGG_ERR_OVERFLOW;
+  int64_t NQ = (int64_t)s->N * L;
+  // token ids and compacted row numbers are int32; tile padding must also fit
+  if (NQ > (int64_t)INT32_MAX - 2 * kTileRows) return AGG_ERR_OVERFLOW;
+  // element offsets are 64-bit in the kernels, but keep one tensor under 2^62 bytes
+  if ((int64_t)s->B * s->H > ((int64_t)1 << 40) / NQ) return AGG_ERR_OVERFLOW;
+
+  g->B = s->B;
+  g->N = s->N;
+  g->L = (int32_t)L;
+  g->P = s->n_special;
+  g->n_h = s->n_h;
+  g->n_w = s->n_w;
+  g->H = s->H;
+  g->s_h = dense ? 1 : s->s_h;
+  g->s_w = dense ? 1 : s->s_w;
+  g->keep_first = dense ? 0 : s->keep_first_frame;
+  // a stride larger than the grid keeps one row/column of windows (edge windows count)
+  g->kw = (int32_t)ceil_div(s->n_w, g->s_w);
+  g->kf = (int32_t)(ceil_div(s->n_h, g->s_h) * g->kw);
+  g->rows_sub = g->P + g->kf;
+  g->dw = g->n_w - g->kw;
+  g->df = (int32_t)(T - g->kf);
+  g->NQ = NQ;
+  int64_t f0 = g->keep_first ? 1 : 0;
+  g->M = f0 * L + ((int64_t)s->N - f0) * g->rows_sub;
+  g->M_pad = ceil_div(g->M, kTileRows) * kTileRows;
+  g->n_dropped = ((int64_t)s->N - f0) * g->df;
+  return AGG_OK;
+}
+
+static bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+}  // namespace agg
+
+using namespace agg;
+
+extern "C" {
+
+const char* agg_status_string(int status) {
+  switch (status) {
+    case AGG_OK: return "ok";
+    case AGG_ERR_NULL: return "a required pointer is NULL";
+    case AGG_ERR_SHAPE: return "invalid shape, stride, scale or flag";
+    case AGG_ERR_UNSUPPORTED: return "unsupported head dimension (D must be 64)";
+    case AGG_ERR_ALIGN: return "tensor pointer is not 16-byte aligned";
+    case AGG_ERR_WORKSPACE: return "workspace too small";
+    case AGG_ERR_OVERFLOW: return "sequence too long for 32-bit token ids";
+    case AGG_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int agg_sigma_to_strides(int sigma, int32_t* s_h, int32_t* s_w) {
+  if (!s_h || !s_w) return AGG_ERR_NULL;
+  // Sec. 4.3: sigma = s_h * s_w with the factorisations the paper lists
+  static const int table[][3] = {{1, 1, 1}, {2, 1, 2}, {4, 2, 2}, {6, 2, 3}, {9, 3, 3}};
+  for (const auto& row : table)
+    if (row[0] == sigma) {
+      *s_h = row[1];
+      *s_w = row[2];
+      return AGG_OK;
+    }
+  return AGG_ERR_SHAPE;
+}
+
+int agg_kv_count(const agg_shape* shape, int64_t* M, int64_t* n_dropped) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (M) *M = g.M;
+  if (n_dropped) *n_dropped = g.n_dropped;
+  return AGG_OK;
+}
+
+int agg_kv_indices_host(const agg_shape* shape, int32_t* idx) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (!idx) return AGG_ERR_NULL;
+  for (int64_t m = 0; m < g.M; ++m) idx[m] = (int32_t)kept_row_to_token(g, m);
+  return AGG_OK;
+}
+
+int agg_dropped_indices_host(const agg_shape* shape, int32_t* idx) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (!idx) return AGG_ERR_NULL;
+  for (int64_t u = 0; u < g.n_dropped; ++u) idx[u] = (int32_t)dropped_to_token(g, u);
+  return AGG_OK;
+}
+
+int agg_kv_compact_bytes(const agg_shape* shape, size_t* bytes, int64_t* M_pad) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (bytes) *bytes = (size_t)g.B * g.H * g.M_pad * kHeadDim * 2;
+  if (M_pad) *M_pad = g.M_pad;
+  return AGG_OK;
+}
+
+int64_t agg_kc_offset(int64_t m, int32_t d) { return kc_offset(m, d); }
+int64_t agg_vc_offset(int64_t m, int32_t d) { return vc_offset(m, d); }
+
+size_t agg_workspace_bytes(const agg_shape* shape) {
+  Geom g;
+  if (make_geom(shape, &g, false) != AGG_OK) return 0;
+  // [B][chunks][2 (K,V)][H*D] float partial sums; never zero so that a valid pointer is required
+  size_t n = (size_t)g.B * (size_t)mean_chunks(g) * 2 * g.H * kHeadDim * sizeof(float);
+  return n ? n : 256;
+}
+
+size_t agg_dense_workspace_bytes(const agg_shape* shape) {
+  Geom g;
+  if (make_geom(shape, &g, true) != AGG_OK) return 0;
+  return 2 * (size_t)g.B * g.H * g.M_pad * kHeadDim * 2;
+}
+
+int agg_kv_subsample(const agg_shape* shape, const void* K, const void* V, void* Kc, void* Vc,
+                     int32_t* idx, float* kmean, float* vmean, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (!K || !V || !Kc || !Vc || !kmean || !vmean || !workspace) return AGG_ERR_NULL;
+  if (misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) || misaligned(workspace) ||
+      ((uintptr_t)kmean & 3u) || ((uintptr_t)vmean & 3u) || ((uintptr_t)idx & 3u))
+    return AGG_ERR_ALIGN;
+  if (workspace_bytes < agg_workspace_bytes(shape)) return AGG_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (launch_gather(g, K, V, Kc, Vc, idx, st) != hipSuccess) return AGG_ERR_LAUNCH;
+  if (launch_mean(g, K, V, kmean, vmean, workspace, st) != hipSuccess) return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
+int agg_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V,
+                        const void* Kc, const void* Vc, const float* kmean, const float* vmean,
+                        void* O, float* lse, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (!Q || !K || !V || !Kc || !Vc || !kmean || !vmean || !O) return AGG_ERR_NULL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) ||
+      misaligned(O) || ((uintptr_t)kmean & 15u) || ((uintptr_t)vmean & 15u) ||
+      ((uintptr_t)lse & 3u))
+    return AGG_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (launch_attn(g, shape->flags, shape->scale, shape->mean_logit_bias, Q, K, V, Kc, Vc, kmean,
+                  vmean, O, lse, st) != hipSuccess)
+    return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
+int agg_dense_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V,
+                              void* O, float* lse, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  Geom g;
+  int rc = make_geom(shape, &g, true);
+  if (rc != AGG_OK) return rc;
+  if (!Q || !K || !V || !O || !workspace) return AGG_ERR_NULL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(workspace) ||
+      ((uintptr_t)lse & 3u))
+    return AGG_ERR_ALIGN;
+  if (workspace_bytes < agg_dense_workspace_bytes(shape)) return AGG_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  size_t one = (size_t)g.B * g.H * g.M_pad * kHeadDim * 2;
+  void* Kf = workspace;
+  void* Vf = (char*)workspace + one;
+  // repack every row (nothing dropped), then the same attention kernel with no extras
+  if (launch_gather(g, K, V, Kf, Vf, nullptr, st) != hipSuccess) return AGG_ERR_LAUNCH;
+  if (launch_attn(g, 0u, shape->scale, 0.0f, Q, K, V, Kf, Vf, nullptr, nullptr, O, lse, st) !=
+      hipSuccess)
+    return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,329 @@
+// Flash-style forward kernel for subsampled global attention (AVGGT Sec. 4.3):
+// every query attends to the compacted key/value set, plus -- inside the same
+// softmax -- its own key/value when its token was dropped and the mean pair of
+// all dropped patches.  With an un-subsampled compacted set and no extras the
+// same kernel is ordinary global attention (Sec. 4.2).
+//
+// Mapping to gfx950
+//   * One workgroup = 4 wavefronts = 256 queries of one (batch, head); each
+//     wavefront owns 64 queries (two 32-wide MFMA column blocks) for the whole
+//     key loop and keeps Q, the running max/sum and the output accumulator in
+//     registers.
+//   * The score tile is computed transposed, S^T = K * Q^T, with
+//     v_mfma_f32_32x32x16_bf16: a lane then holds 16 keys of ONE query, so the
+//     row max/sum are in-register reductions plus one exchange with lane^32,
+//     and the exponentiated tile is already in the B-operand layout of the
+//     second product O^T += V^T * P^T.  P never touches LDS.
+//   * K/V arrive in "fragment order" (agg.h): a 64-key tile is a linear 8 KiB
+//     copy into LDS and every MFMA A operand is one conflict-free 16-byte read.
+//   * The extras are folded in as the INITIAL state of the online softmax
+//     (running max, running sum, accumulator), so the key loop is unmodified
+//     and the three parts share one normalisation by construction.
+//   * Workgroups are numbered so that the 8 XCDs each stream a different
+//     (batch, head): all workgroups resident on one XCD read the same K/V
+//     stream and share it through that XCD's L2.
+#include "agg_internal.h"
+
+namespace agg {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kAttnThreads = 256;
+constexpr int kQTile = 256;  // queries per workgroup
+constexpr int kXcds = 8;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+union Frag {
+  u32x4 u;
+  bf16x8 h;
+};
+
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+  f32x2 p = {lo, hi};
+  bf16x2 h = __builtin_convertvector(p, bf16x2);  // round to nearest even
+  return __builtin_bit_cast(uint32_t, h);
+}
+__device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
+    Geom g, uint32_t flags, float qscale, float mean_bias2, const uint16_t* __restrict__ Q,
+    const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    const uint16_t* __restrict__ Kc, const uint16_t* __restrict__ Vc,
+    const float* __restrict__ kmean, const float* __restrict__ vmean, uint16_t* __restrict__ O,
+    float* __restrict__ lse, int nqt, int npairs) {
+  __shared__ __align__(16) uint16_t sK[2][kTileElems];
+  __shared__ __align__(16) uint16_t sV[2][kTileElems];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int l32 = lane & 31;
+  const int g2 = lane >> 5;
+
+  // workgroup -> ((batch, head) pair, query tile); consecutive ids go to consecutive XCDs
+  const int bid = blockIdx.x;
+  const int xcd = bid % kXcds;
+  const int seq = bid / kXcds;
+  const int pair = (seq / nqt) * kXcds + xcd;
+  const int qt = seq % nqt;
+  if (pair >= npairs) return;  // uniform for the whole workgroup, before any barrier
+  const int b = pair / g.H;
+  const int h = pair % g.H;
+
+  const int64_t ntiles = g.M_pad / kTileRows;
+  const int64_t bh_off = ((int64_t)b * g.H + h) * g.M_pad * kHeadDim;
+  const u32x4* kc4 = reinterpret_cast<const u32x4*>(Kc + bh_off);
+  const u32x4* vc4 = reinterpret_cast<const u32x4*>(Vc + bh_off);
+
+  // ---- Q fragments (B operand of S^T = K Q^T), pre-multiplied by scale*log2(e) ----
+  Frag Qf[2][4];
+  int64_t qrow[2];
+  int64_t qbase[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    int64_t q = (int64_t)qt * kQTile + wave * 64 + qb * 32 + l32;
+    qrow[qb] = q;
+    int64_t qc = q < g.NQ ? q : g.NQ - 1;  // tail rows recompute the last query, never stored
+    qbase[qb] = (((int64_t)b * g.NQ + qc) * g.H + h) * kHeadDim;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4 raw = *reinterpret_cast<const u32x4*>(Q + qbase[qb] + ks * 16 + g2 * 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        Qf[qb][ks].u[i] = pack_bf16(bf16_lo(raw[i]) * qscale, bf16_hi(raw[i]) * qscale);
+    }
+  }
+
+  // ---- online-softmax state; the extras (self term, mean term) are its initial value ----
+  float m_run[2] = {-INFINITY, -INFINITY};
+  float l_part[2] = {0.f, 0.f};  // this lane's share of the row sum (lanes l and l^32 split a row)
+  f32x16 Oacc[2][2];             // [query block][channel block]: O^T, channel = 32db + 8(r/4) + 4g2 + r%4
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) Oacc[qb][db][r] = 0.f;
+
+  const bool use_mean = (flags & AGG_MEAN) && g.n_dropped > 0;
+  const bool use_diag = (flags & AGG_DIAG) && g.n_dropped > 0;
+  if (use_mean || use_diag) {
+    const float* km = kmean + ((int64_t)b * g.H + h) * kHeadDim;
+    const float* vm = vmean + ((int64_t)b * g.H + h) * kHeadDim;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const bool dropped = use_diag && qrow[qb] < g.NQ && token_is_dropped(g, qrow[qb]);
+      float dot_self = 0.f, dot_mean = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int d0 = ks * 16 + g2 * 8;
+        float qv[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          qv[2 * i] = bf16_lo(Qf[qb][ks].u[i]);
+          qv[2 * i + 1] = bf16_hi(Qf[qb][ks].u[i]);
+        }
+        if (use_mean) {
+          f32x4 a = *reinterpret_cast<const f32x4*>(km + d0);
+          f32x4 c = *reinterpret_cast<const f32x4*>(km + d0 + 4);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dot_mean += qv[i] * a[i] + qv[4 + i] * c[i];
+        }
+        if (dropped) {
+          u32x4 kr = *reinterpret_cast<const u32x4*>(K + qbase[qb] + d0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            dot_self += qv[2 * i] * bf16_lo(kr[i]) + qv[2 * i + 1] * bf16_hi(kr[i]);
+        }
+      }
+      // lanes l and l^32 hold the two halves of the channel range
+      dot_self += __shfl_xor(dot_self, 32);
+      dot_mean += __shfl_xor(dot_mean, 32);
+      const float l_self = dropped ? dot_self : -INFINITY;
+      const float l_mean = use_mean ? dot_mean + mean_bias2 : -INFINITY;
+      const float m0 = fmaxf(l_self, l_mean);
+      if (m0 > -INFINITY) {
+        const float w_self = dropped ? fast_exp2(l_self - m0) : 0.f;
+        const float w_mean = use_mean ? fast_exp2(l_mean - m0) : 0.f;
+        m_run[qb] = m0;
+        l_part[qb] = (g2 == 0) ? (w_self + w_mean) : 0.f;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const int d0 = 32 * db + 8 * r4 + 4 * g2;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            if (use_mean) {
+              f32x4 mv = *reinterpret_cast<const f32x4*>(vm + d0);
+              acc = mv * w_mean;
+            }
+            if (dropped) {
+              u32x2 vr = *reinterpret_cast<const u32x2*>(V + qbase[qb] + d0);
+              acc[0] += w_self * bf16_lo(vr[0]);
+              acc[1] += w_self * bf16_hi(vr[0]);
+              acc[2] += w_self * bf16_lo(vr[1]);
+              acc[3] += w_self * bf16_hi(vr[1]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) Oacc[qb][db][r4 * 4 + i] = acc[i];
+          }
+      }
+    }
+  }
+
+  // ---- key loop: double-buffered LDS tiles, next tile prefetched into registers ----
+  u32x4 pk0, pk1, pv0, pv1;
+  pk0 = kc4[tid];
+  pk1 = kc4[tid + kAttnThreads];
+  pv0 = vc4[tid];
+  pv1 = vc4[tid + kAttnThreads];
+  {
+    u32x4* dk = reinterpret_cast<u32x4*>(sK[0]);
+    u32x4* dv = reinterpret_cast<u32x4*>(sV[0]);
+    dk[tid] = pk0;
+    dk[tid + kAttnThreads] = pk1;
+    dv[tid] = pv0;
+    dv[tid + kAttnThreads] = pv1;
+  }
+  __syncthreads();
+
+  for (int64_t t = 0; t < ntiles; ++t) {
+    const int buf = (int)(t & 1);
+    const bool more = (t + 1 < ntiles);
+    if (more) {
+      const u32x4* nk = kc4 + (t + 1) * (kTileElems / 8);
+      const u32x4* nv = vc4 + (t + 1) * (kTileElems / 8);
+      pk0 = nk[tid];
+      pk1 = nk[tid + kAttnThreads];
+      pv0 = nv[tid];
+      pv1 = nv[tid + kAttnThreads];
+    }
+    const u32x4* tk = reinterpret_cast<const u32x4*>(sK[buf]);
+    const u32x4* tv = reinterpret_cast<const u32x4*>(sV[buf]);
+    const int valid = (int)((g.M - t * kTileRows) < kTileRows ? (g.M - t * kTileRows) : kTileRows);
+
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 S[2];
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) S[qb][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        Frag a;
+        a.u = tk[((kb * 4 + ks) * 2 + g2) * 32 + l32];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+          S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.h, Qf[qb][ks].h, S[qb], 0, 0, 0);
+      }
+      if (valid < kTileRows) {  // zero-padded tail rows of the last tile
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int km = 32 * kb + 8 * (r >> 2) + 4 * g2 + (r & 3);
+          if (km >= valid) {
+            S[0][r] = -INFINITY;
+            S[1][r] = -INFINITY;
+          }
+        }
+      }
+      Frag Pf[2][2];
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        float mx = S[qb][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[qb][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[qb], mx);  // finite: row 0 of the set is always valid
+        const float alpha = fast_exp2(m_run[qb] - m_new);
+        m_run[qb] = m_new;
+        float p[16];
+        float rowsum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          p[r] = fast_exp2(S[qb][r] - m_new);
+          rowsum += p[r];
+        }
+        l_part[qb] = l_part[qb] * alpha + rowsum;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) Oacc[qb][db][r] *= alpha;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            Pf[qb][hf].u[i] = pack_bf16(p[hf * 8 + 2 * i], p[hf * 8 + 2 * i + 1]);
+      }
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int tt = kb * 2 + hf;
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          Frag a;
+          a.u = tv[(tt * 2 + g2) * 64 + db * 32 + l32];
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb)
+            Oacc[qb][db] =
+                __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.h, Pf[qb][hf].h, Oacc[qb][db], 0, 0, 0);
+        }
+      }
+    }
+
+    if (more) {
+      u32x4* dk = reinterpret_cast<u32x4*>(sK[buf ^ 1]);
+      u32x4* dv = reinterpret_cast<u32x4*>(sV[buf ^ 1]);
+      dk[tid] = pk0;
+      dk[tid + kAttnThreads] = pk1;
+      dv[tid] = pv0;
+      dv[tid + kAttnThreads] = pv1;
+    }
+    __syncthreads();
+  }
+
+  // ---- normalise and store ----
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const float l = l_part[qb] + __shfl_xor(l_part[qb], 32);
+    const float inv = 1.0f / l;
+    if (qrow[qb] < g.NQ) {
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int d0 = 32 * db + 8 * r4 + 4 * g2;
+          u32x2 w;
+          w[0] = pack_bf16(Oacc[qb][db][r4 * 4 + 0] * inv, Oacc[qb][db][r4 * 4 + 1] * inv);
+          w[1] = pack_bf16(Oacc[qb][db][r4 * 4 + 2] * inv, Oacc[qb][db][r4 * 4 + 3] * inv);
+          *reinterpret_cast<u32x2*>(O + qbase[qb] + d0) = w;
+        }
+      if (lse && g2 == 0)
+        lse[((int64_t)b * g.H + h) * g.NQ + qrow[qb]] = (m_run[qb] + log2f(l)) * kLn2;
+    }
+  }
+}
+
+hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bias, const void* Q,
+                       const void* K, const void* V, const void* Kc, const void* Vc,
+                       const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st) {
+  const int nqt = (int)((g.NQ + kQTile - 1) / kQTile);
+  const int npairs = g.B * g.H;
+  const int64_t groups = (int64_t)((npairs + kXcds - 1) / kXcds) * kXcds * nqt;
+  if (groups > 0x7FFFFFFF) return hipErrorInvalidConfiguration;
+  hipLaunchKernelGGL(sga_attn_kernel, dim3((unsigned)groups), dim3(kAttnThreads), 0, st, g, flags,
+                     scale * kLog2e, mean_bias * kLog2e, (const uint16_t*)Q, (const uint16_t*)K,
+                     (const uint16_t*)V, (const uint16_t*)Kc, (const uint16_t*)Vc, kmean, vmean,
+                     (uint16_t*)O, lse, nqt, npairs);
+  return hipGetLastError();
+}
+
+}  // namespace agg

@@ -1,0 +1,123 @@
+// Internal declarations shared by the host API and the HIP kernels of libagg.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "agg.h"
+
+namespace agg {
+
+constexpr int kHeadDim = 64;    // the only head dimension the kernels are written for
+constexpr int kTileRows = 64;   // compacted rows per fragment-order tile
+constexpr int kTileElems = kTileRows * kHeadDim;  // 4096 bf16 = 8 KiB
+
+// Geometry derived once on the host and passed to kernels by value.
+struct Geom {
+  int32_t B, N, L, P, n_h, n_w, H;
+  int32_t s_h, s_w;
+  int32_t keep_first;   // 1 when frame 0 is kept whole
+  int32_t kw;           // kept patch columns per grid row  = ceil(n_w / s_w)
+  int32_t kf;           // kept patches per subsampled frame = ceil(n_h/s_h) * kw
+  int32_t rows_sub;     // kept rows per subsampled frame    = P + kf
+  int32_t dw;           // dropped patches in a grid row that keeps some columns = n_w - kw
+  int32_t df;           // dropped patches per subsampled frame = n_h*n_w - kf
+  int64_t NQ;           // tokens per sequence = N * L
+  int64_t M;            // kept rows per sequence
+  int64_t M_pad;        // M rounded up to a multiple of kTileRows
+  int64_t n_dropped;    // dropped patches per sequence
+};
+
+// Compacted row m (0 <= m < M)  ->  token id of the sequence.  The kept set in
+// ascending order is: frame 0 whole (if kept), then per frame its special tokens
+// followed by the kept patches in row-major order (Sec. 4.3).
+__host__ __device__ inline int64_t kept_row_to_token(const Geom& g, int64_t m) {
+  int64_t frame;
+  int32_t j;
+  if (g.keep_first) {
+    if (m < g.L) return m;
+    int64_t r = m - g.L;
+    frame = 1 + r / g.rows_sub;
+    j = (int32_t)(r % g.rows_sub);
+  } else {
+    frame = m / g.rows_sub;
+    j = (int32_t)(m % g.rows_sub);
+  }
+  int32_t slot;
+  if (j < g.P) {
+    slot = j;
+  } else {
+    int32_t q = j - g.P;
+    int32_t row = (q / g.kw) * g.s_h;
+    int32_t col = (q % g.kw) * g.s_w;
+    slot = g.P + row * g.n_w + col;
+  }
+  return frame * g.L + slot;
+}
+
+// Dropped patch number u (0 <= u < n_dropped, ascending token order) -> token id.
+// A grid row r with r % s_h != 0 is dropped entirely (n_w patches); a row with
+// r % s_h == 0 drops the columns c with c % s_w != 0 (dw patches).
+__host__ __device__ inline int64_t dropped_to_token(const Geom& g, int64_t u) {
+  int64_t frame = (g.keep_first ? 1 : 0) + u / g.df;
+  int32_t j = (int32_t)(u % g.df);
+  // rows come in groups of s_h: the first keeps some columns, the rest are dropped whole
+  int32_t per_group = g.dw + (g.s_h - 1) * g.n_w;  // > 0 whenever anything is dropped
+  if (per_group < 1) per_group = 1;
+  int32_t grp = j / per_group;
+  int32_t w = j % per_group;
+  int32_t row, col;
+  if (w < g.dw) {
+    row = grp * g.s_h;
+    // w-th column with c % s_w != 0:  c = w + w/(s_w-1) + 1
+    col = w + w / (g.s_w > 1 ? g.s_w - 1 : 1) + 1;
+  } else {
+    int32_t x = w - g.dw;
+    row = grp * g.s_h + 1 + x / g.n_w;
+    col = x % g.n_w;
+  }
+  return frame * g.L + g.P + (int64_t)row * g.n_w + col;
+}
+
+// 1 when token `tok` is a patch that is not in the kept set.
+__host__ __device__ inline int token_is_dropped(const Geom& g, int64_t tok) {
+  int64_t frame = tok / g.L;
+  int32_t slot = (int32_t)(tok % g.L);
+  if (slot < g.P) return 0;
+  if (frame == 0 && g.keep_first) return 0;
+  int32_t p = slot - g.P;
+  int32_t row = p / g.n_w, col = p % g.n_w;
+  return (row % g.s_h != 0) || (col % g.s_w != 0);
+}
+
+// Element offsets of (row m, channel d) inside one (batch, head) block of the
+// fragment-order compacted tensors (documented in agg.h).
+__host__ __device__ inline int64_t kc_offset(int64_t m, int32_t d) {
+  int64_t tile = m / kTileRows;
+  int32_t km = (int32_t)(m % kTileRows);
+  int32_t chunk = (((km / 32) * 4 + d / 16) * 2 + (d % 16) / 8) * 32 + km % 32;
+  return tile * kTileElems + chunk * 8 + d % 8;
+}
+__host__ __device__ inline int64_t vc_offset(int64_t m, int32_t d) {
+  int64_t tile = m / kTileRows;
+  int32_t km = (int32_t)(m % kTileRows);
+  int32_t u = km % 16;
+  int32_t chunk = ((km / 16) * 2 + (u % 8) / 4) * 64 + d;
+  return tile * kTileElems + chunk * 8 + (u / 8) * 4 + u % 4;
+}
+
+// Host-side validation + geometry (agg_api.cpp).
+int make_geom(const agg_shape* s, Geom* g, bool dense);
+
+// Kernel launchers (each returns hipGetLastError() of its launches).
+hipError_t launch_gather(const Geom& g, const void* K, const void* V, void* Kc, void* Vc,
+                         int32_t* idx, hipStream_t st);
+hipError_t launch_mean(const Geom& g, const void* K, const void* V, float* kmean, float* vmean,
+                       void* workspace, hipStream_t st);
+hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bias, const void* Q,
+                       const void* K, const void* V, const void* Kc, const void* Vc,
+                       const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st);
+
+int mean_chunks(const Geom& g);  // number of partial-sum blocks the mean kernel uses
+
+}  // namespace agg

@@ -1,0 +1,103 @@
+"""Buffer plumbing around the C ABI for tests, the smoke check and the benchmark.
+
+Allocates the device buffers the library's calls need (PyTorch owns the memory),
+and decodes the fragment-order compacted tensors for comparison.  No arithmetic
+of the method happens here.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+
+from . import binding as agg
+
+
+def shape_of(w, flags=agg.AGG_DIAG | agg.AGG_MEAN, s_h=None, s_w=None, keep_first_frame=None,
+             mean_logit_bias=0.0, scale=None) -> agg.agg_shape:
+    """agg_shape for a ``inputs.Workload`` (strides / first-frame rule overridable)."""
+    return agg.make_shape(
+        w.B, w.N, w.n_h, w.n_w, w.n_special, w.H, w.D,
+        w.s_h if s_h is None else s_h, w.s_w if s_w is None else s_w,
+        w.keep_first_frame if keep_first_frame is None else keep_first_frame,
+        flags, scale, mean_logit_bias)
+
+
+@dataclass
+class SgaBuffers:
+    shape: agg.agg_shape
+    M: int
+    M_pad: int
+    n_dropped: int
+    Kc: torch.Tensor
+    Vc: torch.Tensor
+    idx: torch.Tensor
+    kmean: torch.Tensor
+    vmean: torch.Tensor
+    workspace: torch.Tensor
+    O: torch.Tensor
+    lse: torch.Tensor
+
+
+def alloc(shape: agg.agg_shape, device="cuda", with_lse=True, poison=False) -> SgaBuffers:
+    M, nd = agg.agg_kv_count(shape)
+    nbytes, m_pad = agg.agg_kv_compact_bytes(shape)
+    B, H, D, NQ = shape.B, shape.H, shape.D, shape.NQ
+    mk = torch.empty
+    Kc = mk(nbytes // 2, dtype=torch.bfloat16, device=device)
+    Vc = mk(nbytes // 2, dtype=torch.bfloat16, device=device)
+    idx = mk(M, dtype=torch.int32, device=device)
+    kmean = mk((B, H, D), dtype=torch.float32, device=device)
+    vmean = mk((B, H, D), dtype=torch.float32, device=device)
+    ws = mk(agg.agg_workspace_bytes(shape), dtype=torch.uint8, device=device)
+    O = mk((B, NQ, H, D), dtype=torch.bfloat16, device=device)
+    lse = mk((B, H, NQ), dtype=torch.float32, device=device) if with_lse else None
+    if poison:  # make stale or unwritten memory visible to the comparison
+        for t in (Kc, Vc, kmean, vmean, O):
+            t.fill_(float("nan"))
+        idx.fill_(-7)
+        ws.fill_(0xFF)
+        if lse is not None:
+            lse.fill_(float("nan"))
+    return SgaBuffers(shape, M, m_pad, nd, Kc, Vc, idx, kmean, vmean, ws, O, lse)
+
+
+def subsample(buf: SgaBuffers, K, V, stream=None):
+    agg.agg_kv_subsample(buf.shape, K, V, buf.Kc, buf.Vc, buf.idx, buf.kmean, buf.vmean,
+                         buf.workspace, buf.workspace.numel(), stream)
+
+
+def attend(buf: SgaBuffers, Q, K, V, stream=None):
+    agg.agg_global_attn_fwd(buf.shape, Q, K, V, buf.Kc, buf.Vc, buf.kmean, buf.vmean, buf.O,
+                            buf.lse, stream)
+
+
+def sga_forward(shape, Q, K, V, poison=False) -> SgaBuffers:
+    """One pass of the whole path: gather + mean terms, then attention."""
+    buf = alloc(shape, Q.device, poison=poison)
+    subsample(buf, K, V)
+    attend(buf, Q, K, V)
+    return buf
+
+
+def dense_forward(shape, Q, K, V, with_lse=True):
+    B, H, D, NQ = shape.B, shape.H, shape.D, shape.NQ
+    O = torch.empty((B, NQ, H, D), dtype=torch.bfloat16, device=Q.device)
+    lse = torch.empty((B, H, NQ), dtype=torch.float32, device=Q.device) if with_lse else None
+    nws = agg.agg_dense_workspace_bytes(shape)
+    ws = torch.empty(nws, dtype=torch.uint8, device=Q.device)
+    agg.agg_dense_global_attn_fwd(shape, Q, K, V, O, lse, ws, nws)
+    return O, lse
+
+
+def decode_compact(flat: torch.Tensor, B: int, H: int, M: int, M_pad: int, which: str) -> torch.Tensor:
+    """Fragment-order Kc ('k') or Vc ('v') -> plain [B, H, M_pad, 64] (layout of agg.h)."""
+    nt = M_pad // 64
+    x = flat.view(B, H, nt, 4096)
+    if which == "k":
+        # [kb(2)][ks(4)][g(2)][key(32)][e(8)] ; row = kb*32+key ; channel = ks*16 + g*8 + e
+        x = x.view(B, H, nt, 2, 4, 2, 32, 8).permute(0, 1, 2, 3, 6, 4, 5, 7)
+        return x.reshape(B, H, M_pad, 64)
+    # [t(4)][g(2)][d(64)][e_hi(2)][e_lo(4)] ; row = 16t + 8e_hi + 4g + e_lo
+    x = x.view(B, H, nt, 4, 2, 64, 2, 4).permute(0, 1, 2, 3, 6, 4, 7, 5)
+    return x.reshape(B, H, M_pad, 64)

@@ -1,0 +1,227 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Index lists and the compacted copies must be bit-exact;
+outputs must agree within max-abs 2e-2 and mean-abs 2e-3 on unit-scale values
+(bf16 operands, float32 accumulation, probabilities rounded to bf16 for the
+second product); log-sum-exp within 1e-2; mean terms within 1e-6 + 1e-5*|mean|."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sga_oracle as orc
+from paper_2512_02541_amd import binding as agg
+from paper_2512_02541_amd import harness, inputs
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 2e-2
+MEAN_ABS = 2e-3
+LSE_ABS = 1e-2
+
+
+def oshape(s):
+    return orc.Shape(s.B, s.N, s.n_h, s.n_w, s.n_special, s.H, s.D, s.s_h, s.s_w,
+                     s.keep_first_frame, s.flags, s.scale, s.mean_logit_bias)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def check_subsample(shape, buf, kb, vb):
+    """idx / Kc / Vc bit-exact, means close; returns the oracle's pieces."""
+    o = oshape(shape)
+    idx = orc.kept_indices(o)
+    M, nd = orc.counts(o)
+    assert (buf.M, buf.n_dropped) == (M, nd)
+    assert (buf.idx.cpu().numpy() == idx).all(), "kept index list differs"
+    Kc, Vc = orc.gather(o, kb, vb, idx)
+    got_k = harness.decode_compact(buf.Kc, shape.B, shape.H, M, buf.M_pad, "k")
+    got_v = harness.decode_compact(buf.Vc, shape.B, shape.H, M, buf.M_pad, "v")
+    assert (inputs.bf16_bits(got_k[:, :, :M]) == Kc).all(), "compacted K differs"
+    assert (inputs.bf16_bits(got_v[:, :, :M]) == Vc).all(), "compacted V differs"
+    if buf.M_pad > M:  # padding rows are zeros
+        assert (inputs.bf16_bits(got_k[:, :, M:]) == 0).all()
+        assert (inputs.bf16_bits(got_v[:, :, M:]) == 0).all()
+    km, vm = orc.mean(o, kb, vb)
+    gk = buf.kmean.cpu().numpy().astype(np.float64)
+    gv = buf.vmean.cpu().numpy().astype(np.float64)
+    assert (np.abs(gk - km) <= 1e-6 + 1e-5 * np.abs(km)).all(), np.abs(gk - km).max()
+    assert (np.abs(gv - vm) <= 1e-6 + 1e-5 * np.abs(vm)).all(), np.abs(gv - vm).max()
+    return idx, nd, Kc, Vc, km, vm
+
+
+def check_output(got_o, got_lse, want_o, want_lse, rows, what, lse_rel=0.0):
+    g = got_o[:, rows].float().cpu().numpy().astype(np.float64)
+    err = np.abs(g - want_o)
+    assert np.isfinite(g).all(), what
+    assert err.max() <= MAX_ABS, (what, err.max())
+    assert err.mean() <= MEAN_ABS, (what, err.mean())
+    if got_lse is not None:
+        gl = got_lse[:, :, rows].cpu().numpy().astype(np.float64)
+        lse_err = np.abs(gl - want_lse)
+        assert (lse_err <= LSE_ABS + lse_rel * np.abs(want_lse)).all(), (what, lse_err.max())
+    return err.max(), err.mean()
+
+
+def run_case(shape, q, k, v, rows=None, what="", lse_rel=0.0):
+    say("case %s: B=%d N=%d grid=%dx%d P=%d H=%d strides=(%d,%d) keep_first=%d flags=%d bias=%g" % (
+        what, shape.B, shape.N, shape.n_h, shape.n_w, shape.n_special, shape.H, shape.s_h,
+        shape.s_w, shape.keep_first_frame, shape.flags, shape.mean_logit_bias))
+    buf = harness.sga_forward(shape, q, k, v, poison=True)
+    torch.cuda.synchronize()
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    idx, nd, Kc, Vc, km, vm = check_subsample(shape, buf, kb, vb)
+    if rows is None:
+        rows = np.arange(shape.NQ, dtype=np.int64)
+    want_o, want_lse, _ = orc.attn_rows(oshape(shape), qb, kb, vb, Kc, Vc, km, vm, nd, rows)
+    return check_output(buf.O, buf.lse, want_o, want_lse, rows, what, lse_rel)
+
+
+# ----------------------------------------------------------------------------
+# Tiny configuration: every flag combination, both first-frame rules, every sigma
+# ----------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def tiny_qkv():
+    w = inputs.WORKLOADS["tiny"]
+    return w, inputs.make_qkv(w, "cuda")
+
+
+@pytest.mark.parametrize("sigma", [1, 2, 4, 6, 9])
+@pytest.mark.parametrize("keep_first", [0, 1])
+def test_tiny_all_flags(tiny_qkv, sigma, keep_first):
+    w, (q, k, v) = tiny_qkv
+    s_h, s_w = agg.agg_sigma_to_strides(sigma)
+    for flags in (0, agg.AGG_DIAG, agg.AGG_MEAN, agg.AGG_DIAG | agg.AGG_MEAN):
+        shape = harness.shape_of(w, flags=flags, s_h=s_h, s_w=s_w, keep_first_frame=keep_first)
+        run_case(shape, q, k, v, what="tiny sigma=%d" % sigma)
+
+
+def test_tiny_dense_baseline_and_stride_one_agree(tiny_qkv):
+    w, (q, k, v) = tiny_qkv
+    shape = harness.shape_of(w)
+    O, lse = harness.dense_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    rows = np.arange(shape.NQ, dtype=np.int64)
+    want_o, want_lse = orc.dense_rows(oshape(shape), qb, kb, vb, rows)
+    check_output(O, lse, want_o, want_lse, rows, "dense tiny")
+    # strides (1,1) through the SGA entry point is the same computation, bit for bit
+    s1 = harness.shape_of(w, s_h=1, s_w=1)
+    buf = harness.sga_forward(s1, q, k, v)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.O.view(torch.int16), O.view(torch.int16))
+    assert torch.equal(buf.lse, lse)
+
+
+def test_mean_logit_bias(tiny_qkv):
+    w, (q, k, v) = tiny_qkv
+    _, nd = agg.agg_kv_count(harness.shape_of(w))
+    shape = harness.shape_of(w, flags=agg.AGG_MEAN, mean_logit_bias=math.log(nd))
+    run_case(shape, q, k, v, what="tiny bias=ln|D|")
+
+
+# ----------------------------------------------------------------------------
+# Ragged shapes: head counts that do not fill a head group, batch > 1, grids
+# that leave partial windows, compacted sets shorter than one tile, query
+# counts that are not a multiple of the 256-row query tile.
+# ----------------------------------------------------------------------------
+RAGGED = [
+    # B, N, n_h, n_w, P, H, s_h, s_w, keep_first
+    (2, 3, 5, 7, 2, 3, 2, 3, 1),
+    (1, 1, 4, 4, 1, 1, 3, 3, 0),     # M = 5 rows: far less than one tile
+    (1, 2, 9, 11, 0, 5, 2, 2, 0),    # no special tokens
+    (2, 5, 13, 17, 5, 2, 3, 3, 1),   # NQ = 1130 = 4*256 + 106
+    (1, 4, 8, 8, 5, 16, 1, 2, 1),
+    (1, 3, 6, 6, 5, 4, 7, 7, 0),     # strides larger than the grid: one patch per frame
+    (1, 1, 6, 6, 5, 4, 2, 2, 1),     # single frame kept whole: nothing dropped
+]
+
+
+@pytest.mark.parametrize("case", RAGGED)
+def test_ragged_shapes(case):
+    B, N, n_h, n_w, P, H, s_h, s_w, kf = case
+    shape = agg.make_shape(B, N, n_h, n_w, P, H, 64, s_h, s_w, kf)
+    q, k, v = inputs.iid_qkv(B, shape.NQ, H, 64, seed=500 + N * 7 + H, device="cuda")
+    run_case(shape, q, k, v, what="ragged")
+    O, lse = harness.dense_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    rows = np.arange(shape.NQ, dtype=np.int64)
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    want_o, want_lse = orc.dense_rows(oshape(shape), qb, kb, vb, rows)
+    check_output(O, lse, want_o, want_lse, rows, "ragged dense")
+
+
+def test_large_logits_stay_finite():
+    """Peaked rows: queries aligned with their own key at 6x scale (logits near 50); the
+    online max has to move a long way between tiles without overflow.  The kernel feeds
+    the MFMA with q*scale*log2(e) rounded to bf16, a relative perturbation of at most
+    2^-9 per logit, so the log-sum-exp tolerance grows with its magnitude here."""
+    w = inputs.WORKLOADS["tiny"]
+    q, k, v = inputs.make_qkv(w, "cuda")
+    q = (6.0 * k.float()).to(torch.bfloat16)
+    shape = harness.shape_of(w)
+    run_case(shape, q, k, v, what="peaked", lse_rel=2.0 ** -8)
+
+
+def test_bitwise_reproducible(tiny_qkv):
+    w, (q, k, v) = tiny_qkv
+    shape = harness.shape_of(w)
+    a = harness.sga_forward(shape, q, k, v, poison=True)
+    b = harness.sga_forward(shape, q, k, v, poison=True)
+    torch.cuda.synchronize()
+    for x, y in ((a.O, b.O), (a.Kc, b.Kc), (a.Vc, b.Vc)):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+    for x, y in ((a.lse, b.lse), (a.kmean, b.kmean), (a.vmean, b.vmean), (a.idx, b.idx)):
+        assert torch.equal(x, y)
+
+
+# ----------------------------------------------------------------------------
+# Full-size workloads, in the launch configuration the benchmark times: index
+# list, compacted copies and means in full; attention on a stratified row sample
+# (every query row is independent) against the full compacted set.
+# ----------------------------------------------------------------------------
+def sample_rows(w, tile=256, extra=12, seed=0):
+    L, NQ = w.L, w.NQ
+    rows = set()
+    frames = sorted({0, 1, w.N // 2, w.N - 1})
+    cells = [(0, 0), (0, 1), (1, 0), (1, 1), (2, 2), (2, 3), (w.n_h - 1, w.n_w - 1),
+             (w.n_h - 1, 0), (0, w.n_w - 1), (w.n_h // 2, w.n_w // 2 + 1)]
+    for f in frames:
+        for t in range(w.n_special):
+            rows.add(f * L + t)
+        for r, c in cells:
+            rows.add(f * L + w.n_special + r * w.n_w + c)
+    last_tile = (NQ // tile) * tile
+    for r in (tile - 1, tile, last_tile - 1, last_tile, NQ - 1, NQ - 2):
+        if 0 <= r < NQ:
+            rows.add(r)
+    rng = np.random.default_rng(seed)
+    rows.update(int(x) for x in rng.integers(0, NQ, size=extra))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+@pytest.mark.parametrize("name", ["f100", "f300", "f800"])
+def test_full_size_workloads(name):
+    w = inputs.WORKLOADS[name]
+    say("generating %s" % name)
+    q, k, v = inputs.make_qkv(w, "cuda")
+    shape = harness.shape_of(w)
+    rows = sample_rows(w)
+    if name != "f100":  # keep the oracle's share of the run to seconds
+        rows = rows[:: 2]
+    mx, mn = run_case(shape, q, k, v, rows=rows, what=name)
+    say("%s: %d sampled rows, max-abs %.3e mean-abs %.3e" % (name, len(rows), mx, mn))
+
+
+def test_full_size_dense_baseline():
+    w = inputs.WORKLOADS["f100"]
+    q, k, v = inputs.make_qkv(w, "cuda")
+    shape = harness.shape_of(w)
+    O, lse = harness.dense_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    rows = sample_rows(w)[:: 4]
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    want_o, want_lse = orc.dense_rows(oshape(shape), qb, kb, vb, rows)
+    check_output(O, lse, want_o, want_lse, rows, "dense f100")

@@ -1,0 +1,170 @@
+"""Host-side behaviour of libagg.so, checked without a GPU: exported symbols,
+counts and index lists against the oracle's enumeration, the fragment-order
+offset maps, and every error path that is decided before a launch."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import sga_oracle as orc
+from paper_2512_02541_amd import binding as agg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def oshape(s):
+    return orc.Shape(s.B, s.N, s.n_h, s.n_w, s.n_special, s.H, s.D, s.s_h, s.s_w,
+                     s.keep_first_frame, s.flags, s.scale, s.mean_logit_bias)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "agg.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(agg_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    lib = agg.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(agg.EXPORTS)
+
+
+def test_sigma_table():
+    assert agg.agg_sigma_to_strides(2) == (1, 2)
+    assert agg.agg_sigma_to_strides(4) == (2, 2)
+    assert agg.agg_sigma_to_strides(6) == (2, 3)
+    assert agg.agg_sigma_to_strides(9) == (3, 3)
+    assert agg.agg_sigma_to_strides(1) == (1, 1)
+    for s in (2, 4, 6, 9):
+        assert agg.agg_sigma_to_strides(s) == orc.sigma_to_strides(s)
+    with pytest.raises(agg.AggError) as e:
+        agg.agg_sigma_to_strides(5)
+    assert e.value.status == -2
+
+
+GRIDS = [(1, 1), (1, 5), (4, 4), (5, 7), (7, 3), (16, 16), (37, 37), (28, 37)]
+STRIDES = [(1, 1), (1, 2), (2, 2), (2, 3), (3, 3), (4, 1), (5, 9)]
+
+
+@pytest.mark.parametrize("keep_first", [0, 1])
+@pytest.mark.parametrize("n_special", [0, 5])
+def test_counts_and_indices_match_oracle_enumeration(keep_first, n_special):
+    for (n_h, n_w) in GRIDS:
+        for (s_h, s_w) in STRIDES:
+            for N in (1, 2, 5):
+                s = agg.make_shape(1, N, n_h, n_w, n_special, 16, 64, s_h, s_w, keep_first)
+                o = oshape(s)
+                M, nd = agg.agg_kv_count(s)
+                assert (M, nd) == orc.counts(o), (n_h, n_w, s_h, s_w, N)
+                idx = agg.agg_kv_indices_host(s)
+                assert (idx == orc.kept_indices(o)).all()
+                dropped = agg.agg_dropped_indices_host(s)
+                want = np.setdiff1d(np.arange(s.NQ, dtype=np.int32), idx)
+                assert (dropped == want).all(), (n_h, n_w, s_h, s_w, N)
+                nbytes, m_pad = agg.agg_kv_compact_bytes(s)
+                assert m_pad % 64 == 0 and 0 <= m_pad - M < 64
+                assert nbytes == s.B * s.H * m_pad * 64 * 2
+
+
+def test_workload_counts():
+    from paper_2512_02541_amd.inputs import WORKLOADS
+
+    want = {"tiny": (330, 192), "f100": (71466, 65934), "f300": (110808, 301392),
+            "f333": (122886, 334656), "f800": (140400, 958800)}
+    for name, w in WORKLOADS.items():
+        s = agg.make_shape(w.B, w.N, w.n_h, w.n_w, w.n_special, w.H, w.D, w.s_h, w.s_w,
+                           w.keep_first_frame)
+        assert agg.agg_kv_count(s) == want[name]
+
+
+def test_fragment_order_offsets_are_tile_bijections():
+    for fn in (agg.agg_kc_offset, agg.agg_vc_offset):
+        seen = np.zeros(2 * 4096, dtype=np.int32)
+        for m in range(128):
+            for d in range(64):
+                off = fn(m, d)
+                assert (m // 64) * 4096 <= off < (m // 64 + 1) * 4096
+                seen[off] += 1
+        assert (seen == 1).all()
+    # 16-byte operand groups: K keeps 8 consecutive channels of a row together,
+    # V keeps 8 rows of one channel together
+    for m in range(64):
+        for d0 in range(0, 64, 8):
+            offs = [agg.agg_kc_offset(m, d0 + e) for e in range(8)]
+            assert offs == list(range(offs[0], offs[0] + 8)) and offs[0] % 8 == 0
+    for d in range(64):
+        for t in range(4):
+            for g in range(2):
+                rows = [16 * t + 8 * (e // 4) + 4 * g + e % 4 for e in range(8)]
+                offs = [agg.agg_vc_offset(r, d) for r in rows]
+                assert offs == list(range(offs[0], offs[0] + 8)) and offs[0] % 8 == 0
+
+
+def test_error_paths_before_any_launch():
+    lib = agg.lib()
+    good = agg.make_shape(1, 2, 16, 16, 5, 16, 64, 2, 2)
+    m = ctypes.c_int64(0)
+
+    def count_status(**kw):
+        s = agg.make_shape(1, 2, 16, 16, 5, 16, 64, 2, 2)
+        for k, v in kw.items():
+            setattr(s, k, v)
+        return lib.agg_kv_count(ctypes.byref(s), ctypes.byref(m), None)
+
+    assert count_status() == 0
+    assert lib.agg_kv_count(None, ctypes.byref(m), None) == -1
+    assert count_status(N=0) == -2
+    assert count_status(s_h=0) == -2
+    assert count_status(flags=4) == -2
+    assert count_status(keep_first_frame=2) == -2
+    assert count_status(scale=0.0) == -2
+    assert count_status(scale=float("nan")) == -2
+    assert count_status(D=128) == -3
+    assert count_status(N=2000000, n_h=37, n_w=37) == -6
+    assert "NULL" in agg.status_string(-1)
+    assert agg.status_string(0) == "ok"
+
+    fake = ctypes.c_void_p(0x1000)  # aligned, never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1008)
+    ws = agg.agg_workspace_bytes(good)
+    assert ws > 0
+    sub = lib.agg_kv_subsample
+    assert sub(ctypes.byref(good), None, fake, fake, fake, None, fake, fake, fake, ws, None) == -1
+    assert sub(ctypes.byref(good), fake, fake, fake, fake, None, None, fake, fake, ws, None) == -1
+    assert sub(ctypes.byref(good), odd, fake, fake, fake, None, fake, fake, fake, ws, None) == -4
+    assert sub(ctypes.byref(good), fake, fake, fake, fake, None, fake, fake, fake, ws - 1, None) == -5
+    att = lib.agg_global_attn_fwd
+    assert att(ctypes.byref(good), fake, fake, fake, fake, fake, fake, fake, None, None, None) == -1
+    assert att(ctypes.byref(good), fake, fake, odd, fake, fake, fake, fake, fake, None, None) == -4
+    bad = agg.make_shape(1, 2, 16, 16, 5, 16, 32, 2, 2)
+    assert att(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, fake, fake, None, None) == -3
+    den = lib.agg_dense_global_attn_fwd
+    dws = agg.agg_dense_workspace_bytes(good)
+    assert dws == 2 * 1 * 16 * 576 * 64 * 2  # 522 rows padded to 576
+    assert den(ctypes.byref(good), fake, fake, fake, fake, None, None, dws, None) == -1
+    assert den(ctypes.byref(good), fake, fake, fake, fake, None, fake, dws - 1, None) == -5
+    assert den(ctypes.byref(good), fake, fake, fake, odd, None, fake, dws, None) == -4
+
+
+def test_missing_library_is_an_error(monkeypatch):
+    monkeypatch.setattr(agg, "_lib", None)
+    monkeypatch.setattr(agg, "LIB_PATH", os.path.join(ROOT, "does_not_exist", "libagg.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        agg.lib()
+
+
+def test_decode_compact_inverts_the_documented_layout():
+    import torch
+
+    from paper_2512_02541_amd import harness
+
+    M_pad = 128
+    for which, fn in (("k", agg.agg_kc_offset), ("v", agg.agg_vc_offset)):
+        flat = torch.zeros(2 * 4096, dtype=torch.float32)
+        for m in range(M_pad):
+            for d in range(64):
+                flat[fn(m, d)] = m * 64 + d
+        dec = harness.decode_compact(flat, 1, 1, M_pad, M_pad, which)
+        assert torch.equal(dec.reshape(-1), torch.arange(M_pad * 64, dtype=torch.float32))
