@@ -163,6 +163,48 @@ def read_traffic(name):
     return None
 
 
+def run_only(args, log):
+    """Launches one piece of the path `steps` times, nothing else: short runs for
+    rocprofv3 counter collection.  `copy` is a plain device copy of 1 GiB whose known
+    size calibrates the FETCH_SIZE / WRITE_SIZE counters."""
+    import torch
+
+    from paper_2512_02541_amd import binding as agg
+    from paper_2512_02541_amd import harness, inputs
+
+    if args.only == "copy":
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"only": "copy", "bytes_read": src.numel() * 4,
+                          "bytes_written": src.numel() * 4, "launches": args.steps}))
+        return 0
+    w = inputs.WORKLOADS[args.workload]
+    shape = harness.shape_of(w)
+    q, k, v = inputs.make_qkv(w, "cuda")
+    buf = harness.alloc(shape, "cuda")
+    harness.subsample(buf, k, v)
+    torch.cuda.synchronize()
+    if args.only == "dense":
+        nws = agg.agg_dense_workspace_bytes(shape)
+        ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    for _ in range(args.steps):
+        if args.only == "attn":
+            harness.attend(buf, q, k, v)
+        elif args.only == "gather":
+            harness.subsample(buf, k, v)
+        else:
+            agg.agg_dense_global_attn_fwd(shape, q, k, v, buf.O, None, ws, nws)
+    torch.cuda.synchronize()
+    print(json.dumps({"only": args.only, "workload": args.workload, "launches": args.steps,
+                      "flops_per_launch": sga_flops(w.NQ, buf.M, w.H, w.D),
+                      "gather_bytes": 2.0 * w.NQ * w.H * w.D * 2 + 2.0 * buf.M * w.H * w.D * 2}))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -174,6 +216,8 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=384)
+    ap.add_argument("--only", choices=["attn", "gather", "dense", "copy"], default=None,
+                    help="profiling aid: launch just this piece `steps` times (for rocprofv3 runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1",
@@ -191,6 +235,9 @@ def main():
     from paper_2512_02541_amd import binding as agg
 
     agg.lib()  # fail loudly if the HIP library is missing
+
+    if args.only:
+        return run_only(args, log)
 
     res, ctx = run_workload(args.workload, args.steps, args.warmup, not args.no_dense, log)
     cpu, parity = (None, None)

@@ -72,6 +72,10 @@ def lib():
         raise RuntimeError(
             "libagg.so is missing at %s -- build it with `python -m paper_2512_02541_amd.build`; "
             "there is no fallback path" % LIB_PATH)
+    # PyTorch owns the device memory and streams handed to the library, so the library must
+    # bind to the HIP runtime PyTorch ships: load torch (and with it that runtime) first.
+    import torch  # noqa: F401
+
     L = ctypes.CDLL(LIB_PATH)
     vp, i32p, i64p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
     shp = ctypes.POINTER(agg_shape)

@@ -319,6 +319,7 @@ hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bi
   const int npairs = g.B * g.H;
   const int64_t groups = (int64_t)((npairs + kXcds - 1) / kXcds) * kXcds * nqt;
   if (groups > 0x7FFFFFFF) return hipErrorInvalidConfiguration;
+  (void)hipGetLastError();  // drop any stale error so the check below is this launch's
   hipLaunchKernelGGL(sga_attn_kernel, dim3((unsigned)groups), dim3(kAttnThreads), 0, st, g, flags,
                      scale * kLog2e, mean_bias * kLog2e, (const uint16_t*)Q, (const uint16_t*)K,
                      (const uint16_t*)V, (const uint16_t*)Kc, (const uint16_t*)Vc, kmean, vmean,

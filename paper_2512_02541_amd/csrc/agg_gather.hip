@@ -189,6 +189,7 @@ hipError_t launch_gather(const Geom& g, const void* K, const void* V, void* Kc, 
                          int32_t* idx, hipStream_t st) {
   dim3 grid((unsigned)(g.M_pad / kTileRows), (unsigned)((g.H + kHeadGroup - 1) / kHeadGroup),
             (unsigned)g.B);
+  (void)hipGetLastError();  // drop any stale error so the check below is this launch's
   hipLaunchKernelGGL(gather_kernel, grid, dim3(kGatherThreads), 0, st, g, (const uint16_t*)K,
                      (const uint16_t*)V, (uint16_t*)Kc, (uint16_t*)Vc, idx);
   return hipGetLastError();
@@ -203,12 +204,14 @@ hipError_t launch_mean(const Geom& g, const void* K, const void* V, float* kmean
     const int cpr_b = cpr < kMeanThreads ? cpr : kMeanThreads;
     const int rpp = kMeanThreads / cpr_b;
     dim3 grid((unsigned)nchunks, (unsigned)((cpr + kMeanThreads - 1) / kMeanThreads), (unsigned)g.B);
-    hipLaunchKernelGGL(mean_partial_kernel, grid, dim3(kMeanThreads), 0, st, g, (const uint16_t*)K,
+    (void)hipGetLastError();  // drop any stale error so the check below is this launch's
+  hipLaunchKernelGGL(mean_partial_kernel, grid, dim3(kMeanThreads), 0, st, g, (const uint16_t*)K,
                        (const uint16_t*)V, (float*)workspace, nchunks, cpr_b, rpp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   dim3 grid2((unsigned)((2 * C + 255) / 256), (unsigned)g.B);
+  (void)hipGetLastError();  // drop any stale error so the check below is this launch's
   hipLaunchKernelGGL(mean_final_kernel, grid2, dim3(256), 0, st, g, (const float*)workspace, nchunks,
                      kmean, vmean);
   return hipGetLastError();

@@ -2,7 +2,7 @@
 the same seeded inputs.  Index lists and the compacted copies must be bit-exact;
 outputs must agree within max-abs 2e-2 and mean-abs 2e-3 on unit-scale values
 (bf16 operands, float32 accumulation, probabilities rounded to bf16 for the
-second product); log-sum-exp within 1e-2; mean terms within 1e-6 + 1e-5*|mean|."""
+second product); log-sum-exp within 1e-2 + 2^-9*|lse|; mean terms within 1e-6 + 1e-5*|mean|."""
 import math
 
 import numpy as np
@@ -18,6 +18,7 @@ pytestmark = pytest.mark.gpu
 MAX_ABS = 2e-2
 MEAN_ABS = 2e-3
 LSE_ABS = 1e-2
+LSE_REL = 2.0 ** -9  # q*scale*log2(e) is rounded to bf16 once: each logit moves by <= 2^-9 of its size
 
 
 def oshape(s):
@@ -52,7 +53,7 @@ def check_subsample(shape, buf, kb, vb):
     return idx, nd, Kc, Vc, km, vm
 
 
-def check_output(got_o, got_lse, want_o, want_lse, rows, what, lse_rel=0.0):
+def check_output(got_o, got_lse, want_o, want_lse, rows, what, lse_rel=LSE_REL):
     g = got_o[:, rows].float().cpu().numpy().astype(np.float64)
     err = np.abs(g - want_o)
     assert np.isfinite(g).all(), what
@@ -65,7 +66,7 @@ def check_output(got_o, got_lse, want_o, want_lse, rows, what, lse_rel=0.0):
     return err.max(), err.mean()
 
 
-def run_case(shape, q, k, v, rows=None, what="", lse_rel=0.0):
+def run_case(shape, q, k, v, rows=None, what="", lse_rel=LSE_REL):
     say("case %s: B=%d N=%d grid=%dx%d P=%d H=%d strides=(%d,%d) keep_first=%d flags=%d bias=%g" % (
         what, shape.B, shape.N, shape.n_h, shape.n_w, shape.n_special, shape.H, shape.s_h,
         shape.s_w, shape.keep_first_frame, shape.flags, shape.mean_logit_bias))
