@@ -7,18 +7,33 @@
 // Mapping to gfx950
 //   * One workgroup = 4 wavefronts = 256 queries of one (batch, head); each
 //     wavefront owns 64 queries (two 32-wide MFMA column blocks) for the whole
-//     key loop and keeps Q, the running max/sum and the output accumulator in
+//     key loop and keeps Q, the softmax state and the output accumulator in
 //     registers.
 //   * The score tile is computed transposed, S^T = K * Q^T, with
-//     v_mfma_f32_32x32x16_bf16: a lane then holds 16 keys of ONE query, so the
-//     row max/sum are in-register reductions plus one exchange with lane^32,
-//     and the exponentiated tile is already in the B-operand layout of the
-//     second product O^T += V^T * P^T.  P never touches LDS.
+//     v_mfma_f32_32x32x16_bf16: a lane then holds 16 keys of ONE query, so row
+//     reductions are in-register plus one exchange with lane^32, and the
+//     exponentiated tile is already in the B-operand layout of the second
+//     product O^T += V^T * P^T.  P never touches LDS.
 //   * K/V arrive in "fragment order" (agg.h): a 64-key tile is a linear 8 KiB
 //     copy into LDS and every MFMA A operand is one conflict-free 16-byte read.
-//   * The extras are folded in as the INITIAL state of the online softmax
-//     (running max, running sum, accumulator), so the key loop is unmodified
-//     and the three parts share one normalisation by construction.
+//   * At head dimension 64 the vector ALU, not the matrix core, is the tighter
+//     pipe (one exponential per 256 MFMA flops), so the inner loop is stripped
+//     to exp + convert + sum per score:
+//       - Q is pre-multiplied by scale*log2(e), so scores are base-2 logits;
+//       - the row reference -m is the INITIAL accumulator of the QK^T MFMA, so
+//         the scores come out already shifted;
+//       - the reference is not the running maximum but any value that keeps
+//         exp2(s - m) inside float range: softmax is invariant to it.  It is
+//         raised (with the usual rescale of sum and accumulator) only when a
+//         tile's partial row sum exceeds 2^30, which also covers the first
+//         tile, where m = -inf.  That slow path recomputes the tile's true
+//         maximum; it is wave-uniform and rare;
+//       - row sums are taken from the bf16-rounded probabilities with
+//         v_dot2c_f32_bf16 (two per instruction), the same values the PV MFMA
+//         multiplies.
+//   * The extras are folded in as the initial state of the online softmax
+//     (reference, sum, accumulator), so the key loop is unmodified and the
+//     three parts share one normalisation by construction.
 //   * Workgroups are numbered so that the 8 XCDs each stream a different
 //     (batch, head): all workgroups resident on one XCD read the same K/V
 //     stream and share it through that XCD's L2.
@@ -39,6 +54,7 @@ constexpr int kQTile = 256;  // queries per workgroup
 constexpr int kXcds = 8;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kSumLimit = 1073741824.0f;  // 2^30: partial row sum that triggers a new reference
 
 union Frag {
   u32x4 u;
@@ -53,6 +69,123 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) {
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// acc + lo(w) + hi(w) for a packed bf16 pair
+__device__ inline float add_pair(uint32_t w, float acc) {
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, acc, false);
+}
+
+struct SoftmaxState {
+  float m_ref[2];    // per query block: the reference subtracted from the base-2 logits
+  float l_part[2];   // this lane's share of the row sum (lanes l and l^32 split a row)
+  f32x16 negM[2];    // -m_ref broadcast: initial accumulator of the QK^T MFMA
+  f32x16 Oacc[2][2]; // [query block][channel block] O^T; channel = 32db + 8(r/4) + 4g2 + r%4
+};
+
+// exp2 of 16 shifted scores -> 8 packed bf16 pairs (two B operands) + their sum
+__device__ inline float exp_pack(const f32x16& S, Frag (&Pf)[2]) {
+  float rs = 0.f;
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t w = pack_bf16(fast_exp2(S[hf * 8 + 2 * i]), fast_exp2(S[hf * 8 + 2 * i + 1]));
+      Pf[hf].u[i] = w;
+      rs = add_pair(w, rs);
+    }
+  return rs;
+}
+
+// One 64-key tile held in LDS (tk: K fragments, tv: V fragments) against this
+// wavefront's 64 queries.  `valid` < 64 only on the zero-padded last tile.
+template <bool kMasked>
+__device__ inline void process_tile(const u32x4* __restrict__ tk, const u32x4* __restrict__ tv,
+                                    int valid, const Frag (&Qf)[2][4], SoftmaxState& st, int l32,
+                                    int g2) {
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    Frag a[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) a[ks].u = tk[((kb * 4 + ks) * 2 + g2) * 32 + l32];
+    // one query block at a time keeps a single 16-register score tile live
+    Frag Pf[2][2];
+    float rs[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      f32x16 S =
+          __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0].h, Qf[qb][0].h, st.negM[qb], 0, 0, 0);
+#pragma unroll
+      for (int ks = 1; ks < 4; ++ks)
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks].h, Qf[qb][ks].h, S, 0, 0, 0);
+      if (kMasked) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int km = 32 * kb + 8 * (r >> 2) + 4 * g2 + (r & 3);
+          if (km >= valid) S[r] = -INFINITY;
+        }
+      }
+      rs[qb] = exp_pack(S, Pf[qb]);
+    }
+
+    // Fast path ends here unless some row's probabilities left the safe range
+    // (or the reference is still -inf): then redo this block against its true maximum.
+    const bool bad = !(rs[0] <= kSumLimit) || !(rs[1] <= kSumLimit);
+    if (__any(bad)) {
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        f32x16 T;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) T[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+          T = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks].h, Qf[qb][ks].h, T, 0, 0, 0);
+        if (kMasked) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int km = 32 * kb + 8 * (r >> 2) + 4 * g2 + (r & 3);
+            if (km >= valid) T[r] = -INFINITY;
+          }
+        }
+        float mx = T[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, T[r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(st.m_ref[qb], mx);
+        // m_new is finite except when the block is fully masked and nothing came before,
+        // which cannot happen: compacted row 0 always exists and is in block 0 of tile 0.
+        const float alpha = fast_exp2(st.m_ref[qb] - m_new);  // m_ref = -inf -> 0
+        st.m_ref[qb] = m_new;
+        st.l_part[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) st.Oacc[qb][db][r] *= alpha;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          st.negM[qb][r] = -m_new;
+          T[r] -= m_new;
+        }
+        rs[qb] = exp_pack(T, Pf[qb]);
+      }
+    }
+    st.l_part[0] += rs[0];
+    st.l_part[1] += rs[1];
+
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const int tt = kb * 2 + hf;
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        Frag v;
+        v.u = tv[(tt * 2 + g2) * 64 + db * 32 + l32];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+          st.Oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v.h, Pf[qb][hf].h,
+                                                                     st.Oacc[qb][db], 0, 0, 0);
+      }
+    }
+  }
+}
 
 __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
     Geom g, uint32_t flags, float qscale, float mean_bias2, const uint16_t* __restrict__ Q,
@@ -104,15 +237,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
   }
 
   // ---- online-softmax state; the extras (self term, mean term) are its initial value ----
-  float m_run[2] = {-INFINITY, -INFINITY};
-  float l_part[2] = {0.f, 0.f};  // this lane's share of the row sum (lanes l and l^32 split a row)
-  f32x16 Oacc[2][2];             // [query block][channel block]: O^T, channel = 32db + 8(r/4) + 4g2 + r%4
+  SoftmaxState st;
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
+  for (int qb = 0; qb < 2; ++qb) {
+    st.m_ref[qb] = -INFINITY;
+    st.l_part[qb] = 0.f;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) Oacc[qb][db][r] = 0.f;
+      for (int r = 0; r < 16; ++r) st.Oacc[qb][db][r] = 0.f;
+  }
 
   const bool use_mean = (flags & AGG_MEAN) && g.n_dropped > 0;
   const bool use_diag = (flags & AGG_DIAG) && g.n_dropped > 0;
@@ -154,8 +288,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
       if (m0 > -INFINITY) {
         const float w_self = dropped ? fast_exp2(l_self - m0) : 0.f;
         const float w_mean = use_mean ? fast_exp2(l_mean - m0) : 0.f;
-        m_run[qb] = m0;
-        l_part[qb] = (g2 == 0) ? (w_self + w_mean) : 0.f;
+        st.m_ref[qb] = m0;
+        st.l_part[qb] = (g2 == 0) ? (w_self + w_mean) : 0.f;
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -174,11 +308,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
               acc[3] += w_self * bf16_hi(vr[1]);
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) Oacc[qb][db][r4 * 4 + i] = acc[i];
+            for (int i = 0; i < 4; ++i) st.Oacc[qb][db][r4 * 4 + i] = acc[i];
           }
       }
     }
   }
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) st.negM[qb][r] = -st.m_ref[qb];  // +inf until a reference exists
 
   // ---- key loop: double-buffered LDS tiles, next tile prefetched into registers ----
   u32x4 pk0, pk1, pv0, pv1;
@@ -196,10 +334,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
   }
   __syncthreads();
 
-  for (int64_t t = 0; t < ntiles; ++t) {
+  const int last_valid = (int)(g.M - (ntiles - 1) * kTileRows);  // 1..64
+  for (int64_t t = 0; t + 1 < ntiles; ++t) {
     const int buf = (int)(t & 1);
-    const bool more = (t + 1 < ntiles);
-    if (more) {
+    {
       const u32x4* nk = kc4 + (t + 1) * (kTileElems / 8);
       const u32x4* nv = vc4 + (t + 1) * (kTileElems / 8);
       pk0 = nk[tid];
@@ -207,79 +345,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
       pv0 = nv[tid];
       pv1 = nv[tid + kAttnThreads];
     }
-    const u32x4* tk = reinterpret_cast<const u32x4*>(sK[buf]);
-    const u32x4* tv = reinterpret_cast<const u32x4*>(sV[buf]);
-    const int valid = (int)((g.M - t * kTileRows) < kTileRows ? (g.M - t * kTileRows) : kTileRows);
-
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      f32x16 S[2];
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) S[qb][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        Frag a;
-        a.u = tk[((kb * 4 + ks) * 2 + g2) * 32 + l32];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-          S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.h, Qf[qb][ks].h, S[qb], 0, 0, 0);
-      }
-      if (valid < kTileRows) {  // zero-padded tail rows of the last tile
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int km = 32 * kb + 8 * (r >> 2) + 4 * g2 + (r & 3);
-          if (km >= valid) {
-            S[0][r] = -INFINITY;
-            S[1][r] = -INFINITY;
-          }
-        }
-      }
-      Frag Pf[2][2];
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        float mx = S[qb][0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[qb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[qb], mx);  // finite: row 0 of the set is always valid
-        const float alpha = fast_exp2(m_run[qb] - m_new);
-        m_run[qb] = m_new;
-        float p[16];
-        float rowsum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = fast_exp2(S[qb][r] - m_new);
-          rowsum += p[r];
-        }
-        l_part[qb] = l_part[qb] * alpha + rowsum;
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) Oacc[qb][db][r] *= alpha;
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            Pf[qb][hf].u[i] = pack_bf16(p[hf * 8 + 2 * i], p[hf * 8 + 2 * i + 1]);
-      }
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        const int tt = kb * 2 + hf;
-#pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          Frag a;
-          a.u = tv[(tt * 2 + g2) * 64 + db * 32 + l32];
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb)
-            Oacc[qb][db] =
-                __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.h, Pf[qb][hf].h, Oacc[qb][db], 0, 0, 0);
-        }
-      }
-    }
-
-    if (more) {
+    process_tile<false>(reinterpret_cast<const u32x4*>(sK[buf]),
+                        reinterpret_cast<const u32x4*>(sV[buf]), kTileRows, Qf, st, l32, g2);
+    {
       u32x4* dk = reinterpret_cast<u32x4*>(sK[buf ^ 1]);
       u32x4* dv = reinterpret_cast<u32x4*>(sV[buf ^ 1]);
       dk[tid] = pk0;
@@ -289,11 +357,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
     }
     __syncthreads();
   }
+  {  // last tile, outside the loop: the only one that can hold zero-padded rows
+    const int buf = (int)((ntiles - 1) & 1);
+    process_tile<true>(reinterpret_cast<const u32x4*>(sK[buf]),
+                       reinterpret_cast<const u32x4*>(sV[buf]), last_valid, Qf, st, l32, g2);
+  }
 
   // ---- normalise and store ----
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb) {
-    const float l = l_part[qb] + __shfl_xor(l_part[qb], 32);
+    const float l = st.l_part[qb] + __shfl_xor(st.l_part[qb], 32);
     const float inv = 1.0f / l;
     if (qrow[qb] < g.NQ) {
 #pragma unroll
@@ -302,12 +375,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
         for (int r4 = 0; r4 < 4; ++r4) {
           const int d0 = 32 * db + 8 * r4 + 4 * g2;
           u32x2 w;
-          w[0] = pack_bf16(Oacc[qb][db][r4 * 4 + 0] * inv, Oacc[qb][db][r4 * 4 + 1] * inv);
-          w[1] = pack_bf16(Oacc[qb][db][r4 * 4 + 2] * inv, Oacc[qb][db][r4 * 4 + 3] * inv);
+          w[0] = pack_bf16(st.Oacc[qb][db][r4 * 4 + 0] * inv, st.Oacc[qb][db][r4 * 4 + 1] * inv);
+          w[1] = pack_bf16(st.Oacc[qb][db][r4 * 4 + 2] * inv, st.Oacc[qb][db][r4 * 4 + 3] * inv);
           *reinterpret_cast<u32x2*>(O + qbase[qb] + d0) = w;
         }
       if (lse && g2 == 0)
-        lse[((int64_t)b * g.H + h) * g.NQ + qrow[qb]] = (m_run[qb] + log2f(l)) * kLn2;
+        lse[((int64_t)b * g.H + h) * g.NQ + qrow[qb]] = (st.m_ref[qb] + log2f(l)) * kLn2;
     }
   }
 }
