@@ -10,7 +10,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libagg.so")
+# AGG_LIBRARY_PATH points at another build of the same library (kernel development)
+LIB_PATH = os.environ.get("AGG_LIBRARY_PATH") or os.path.join(_HERE, "libagg.so")
 
 AGG_DIAG = 1
 AGG_MEAN = 2

@@ -7,33 +7,31 @@
 // Mapping to gfx950
 //   * One workgroup = 4 wavefronts = 256 queries of one (batch, head); each
 //     wavefront owns 64 queries (two 32-wide MFMA column blocks) for the whole
-//     key loop and keeps Q, the softmax state and the output accumulator in
-//     registers.
+//     key loop and keeps Q and the output accumulator in registers.
 //   * The score tile is computed transposed, S^T = K * Q^T, with
 //     v_mfma_f32_32x32x16_bf16: a lane then holds 16 keys of ONE query, so row
-//     reductions are in-register plus one exchange with lane^32, and the
+//     sums are in-register plus one exchange with lane^32, and the
 //     exponentiated tile is already in the B-operand layout of the second
 //     product O^T += V^T * P^T.  P never touches LDS.
 //   * K/V arrive in "fragment order" (agg.h): a 64-key tile is a linear 8 KiB
 //     copy into LDS and every MFMA A operand is one conflict-free 16-byte read.
-//   * At head dimension 64 the vector ALU, not the matrix core, is the tighter
-//     pipe (one exponential per 256 MFMA flops), so the inner loop is stripped
-//     to exp + convert + sum per score:
-//       - Q is pre-multiplied by scale*log2(e), so scores are base-2 logits;
-//       - the row reference -m is the INITIAL accumulator of the QK^T MFMA, so
-//         the scores come out already shifted;
-//       - the reference is not the running maximum but any value that keeps
-//         exp2(s - m) inside float range: softmax is invariant to it.  It is
-//         raised (with the usual rescale of sum and accumulator) only when a
-//         tile's partial row sum exceeds 2^30, which also covers the first
-//         tile, where m = -inf.  That slow path recomputes the tile's true
-//         maximum; it is wave-uniform and rare;
-//       - row sums are taken from the bf16-rounded probabilities with
-//         v_dot2c_f32_bf16 (two per instruction), the same values the PV MFMA
-//         multiplies.
-//   * The extras are folded in as the initial state of the online softmax
-//     (reference, sum, accumulator), so the key loop is unmodified and the
-//     three parts share one normalisation by construction.
+//     Three tiles are resident: the one in use, the next one (its first
+//     fragments are fetched a block ahead) and the one being written.
+//   * At head dimension 64 the vector ALU is as loaded as the matrix core (one
+//     exponential per 256 MFMA flops) and a wavefront issues in order, so the
+//     key loop is software-pipelined: while the matrix core runs K Q^T of block
+//     j+1 (then P V of block j), the same wavefront's vector ALU exponentiates
+//     half of block j (then half of block j+1).
+//   * Fast path: Q is pre-multiplied by scale*log2(e) and the probabilities are
+//     exp2 of the raw base-2 logits, with NO reference subtracted: softmax is
+//     invariant to the reference, float/bf16 exponents cover 2^+-126, and the
+//     per-score work shrinks to exp + convert + add.  A row whose sum leaves
+//     [2^-90, 2^90] (logits beyond about +-60 nats) makes the whole workgroup
+//     redo its rows in the general path below; ordinary attention logits never
+//     get there.
+//   * General path: classic online softmax with a running row maximum.
+//   * The extras enter as the initial state (sum, accumulator) of either path, so
+//     the three parts share one normalisation by construction.
 //   * Workgroups are numbered so that the 8 XCDs each stream a different
 //     (batch, head): all workgroups resident on one XCD read the same K/V
 //     stream and share it through that XCD's L2.
@@ -52,9 +50,12 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kAttnThreads = 256;
 constexpr int kQTile = 256;  // queries per workgroup
 constexpr int kXcds = 8;
+constexpr int kLdsTiles = 3;
+constexpr int kChunks = kTileElems / 8;  // 16-byte chunks per K or V tile (512)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kSumLimit = 1073741824.0f;  // 2^30: partial row sum that triggers a new reference
+constexpr float kSumHi = 1.2379400392853803e27f;   // 2^90
+constexpr float kSumLo = 8.077935669463161e-28f;   // 2^-90
 
 union Frag {
   u32x4 u;
@@ -69,121 +70,80 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) {
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-// acc + lo(w) + hi(w) for a packed bf16 pair
-__device__ inline float add_pair(uint32_t w, float acc) {
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, acc, false);
+
+// Workgroup barrier that orders LDS traffic only: global loads issued for a later tile
+// stay in flight across it.
+__device__ inline void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-struct SoftmaxState {
-  float m_ref[2];    // per query block: the reference subtracted from the base-2 logits
-  float l_part[2];   // this lane's share of the row sum (lanes l and l^32 split a row)
-  f32x16 negM[2];    // -m_ref broadcast: initial accumulator of the QK^T MFMA
-  f32x16 Oacc[2][2]; // [query block][channel block] O^T; channel = 32db + 8(r/4) + 4g2 + r%4
-};
+#define AGG_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a).h, (b).h, (c), 0, 0, 0)
 
-// exp2 of 16 shifted scores -> 8 packed bf16 pairs (two B operands) + their sum
-__device__ inline float exp_pack(const f32x16& S, Frag (&Pf)[2]) {
-  float rs = 0.f;
+// K fragments (A operand of S^T = K Q^T) of 32-key block kb of an LDS tile
+__device__ inline void load_k_frags(const u32x4* __restrict__ tk, int kb, int l32, int g2,
+                                    Frag (&a)[4]) {
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) a[ks].u = tk[((kb * 4 + ks) * 2 + g2) * 32 + l32];
+}
+// V fragments (A operand of O^T += V^T P^T) of 32-key block kb; index = hf*2 + db
+__device__ inline void load_v_frags(const u32x4* __restrict__ tv, int kb, int l32, int g2,
+                                    Frag (&v)[4]) {
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+      v[hf * 2 + db].u = tv[((kb * 2 + hf) * 2 + g2) * 64 + db * 32 + l32];
+}
+
+// scores of one 32-key block for both query blocks; the two accumulation chains alternate
+__device__ inline void qk8(const Frag (&a)[4], const Frag (&Qf)[2][4], f32x16& S0, f32x16& S1) {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.f;
+  S0 = AGG_MFMA(a[0], Qf[0][0], z);
+  S1 = AGG_MFMA(a[0], Qf[1][0], z);
+#pragma unroll
+  for (int ks = 1; ks < 4; ++ks) {
+    S0 = AGG_MFMA(a[ks], Qf[0][ks], S0);
+    S1 = AGG_MFMA(a[ks], Qf[1][ks], S1);
+  }
+}
+
+// O^T += V^T P^T for one 32-key block; query block 0 first (its P is the older one)
+__device__ inline void pv8(const Frag (&v)[4], const Frag (&P0)[2], const Frag (&P1)[2],
+                           f32x16 (&O)[2][2]) {
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int db = 0; db < 2; ++db) O[0][db] = AGG_MFMA(v[hf * 2 + db], P0[hf], O[0][db]);
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int db = 0; db < 2; ++db) O[1][db] = AGG_MFMA(v[hf * 2 + db], P1[hf], O[1][db]);
+}
+
+// fast path: probabilities of 16 raw base-2 logits, packed for the PV MFMA, and their sum
+__device__ inline void exp16(const f32x16& S, Frag (&P)[2], float& l0, float& l1) {
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      uint32_t w = pack_bf16(fast_exp2(S[hf * 8 + 2 * i]), fast_exp2(S[hf * 8 + 2 * i + 1]));
-      Pf[hf].u[i] = w;
-      rs = add_pair(w, rs);
+      const float e0 = fast_exp2(S[hf * 8 + 2 * i]);
+      const float e1 = fast_exp2(S[hf * 8 + 2 * i + 1]);
+      P[hf].u[i] = pack_bf16(e0, e1);
+      l0 += e0;
+      l1 += e1;
     }
-  return rs;
 }
 
-// One 64-key tile held in LDS (tk: K fragments, tv: V fragments) against this
-// wavefront's 64 queries.  `valid` < 64 only on the zero-padded last tile.
-template <bool kMasked>
-__device__ inline void process_tile(const u32x4* __restrict__ tk, const u32x4* __restrict__ tv,
-                                    int valid, const Frag (&Qf)[2][4], SoftmaxState& st, int l32,
-                                    int g2) {
+// zero-padded rows of the last tile: key index inside the tile >= valid -> -inf
+__device__ inline void mask16(f32x16& S, int kb, int valid, int g2) {
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
-    Frag a[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) a[ks].u = tk[((kb * 4 + ks) * 2 + g2) * 32 + l32];
-    // one query block at a time keeps a single 16-register score tile live
-    Frag Pf[2][2];
-    float rs[2];
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      f32x16 S =
-          __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0].h, Qf[qb][0].h, st.negM[qb], 0, 0, 0);
-#pragma unroll
-      for (int ks = 1; ks < 4; ++ks)
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks].h, Qf[qb][ks].h, S, 0, 0, 0);
-      if (kMasked) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int km = 32 * kb + 8 * (r >> 2) + 4 * g2 + (r & 3);
-          if (km >= valid) S[r] = -INFINITY;
-        }
-      }
-      rs[qb] = exp_pack(S, Pf[qb]);
-    }
-
-    // Fast path ends here unless some row's probabilities left the safe range
-    // (or the reference is still -inf): then redo this block against its true maximum.
-    const bool bad = !(rs[0] <= kSumLimit) || !(rs[1] <= kSumLimit);
-    if (__any(bad)) {
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        f32x16 T;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) T[r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-          T = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks].h, Qf[qb][ks].h, T, 0, 0, 0);
-        if (kMasked) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int km = 32 * kb + 8 * (r >> 2) + 4 * g2 + (r & 3);
-            if (km >= valid) T[r] = -INFINITY;
-          }
-        }
-        float mx = T[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, T[r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(st.m_ref[qb], mx);
-        // m_new is finite except when the block is fully masked and nothing came before,
-        // which cannot happen: compacted row 0 always exists and is in block 0 of tile 0.
-        const float alpha = fast_exp2(st.m_ref[qb] - m_new);  // m_ref = -inf -> 0
-        st.m_ref[qb] = m_new;
-        st.l_part[qb] *= alpha;
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) st.Oacc[qb][db][r] *= alpha;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          st.negM[qb][r] = -m_new;
-          T[r] -= m_new;
-        }
-        rs[qb] = exp_pack(T, Pf[qb]);
-      }
-    }
-    st.l_part[0] += rs[0];
-    st.l_part[1] += rs[1];
-
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-      const int tt = kb * 2 + hf;
-#pragma unroll
-      for (int db = 0; db < 2; ++db) {
-        Frag v;
-        v.u = tv[(tt * 2 + g2) * 64 + db * 32 + l32];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-          st.Oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v.h, Pf[qb][hf].h,
-                                                                     st.Oacc[qb][db], 0, 0, 0);
-      }
-    }
+  for (int r = 0; r < 16; ++r) {
+    const int km = 32 * kb + 8 * (r >> 2) + 4 * g2 + (r & 3);
+    if (km >= valid) S[r] = -INFINITY;
   }
 }
 
@@ -193,8 +153,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
     const uint16_t* __restrict__ Kc, const uint16_t* __restrict__ Vc,
     const float* __restrict__ kmean, const float* __restrict__ vmean, uint16_t* __restrict__ O,
     float* __restrict__ lse, int nqt, int npairs) {
-  __shared__ __align__(16) uint16_t sK[2][kTileElems];
-  __shared__ __align__(16) uint16_t sV[2][kTileElems];
+  __shared__ __align__(16) uint16_t sK[kLdsTiles][kTileElems];
+  __shared__ __align__(16) uint16_t sV[kLdsTiles][kTileElems];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -212,51 +172,37 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
   const int b = pair / g.H;
   const int h = pair % g.H;
 
-  const int64_t ntiles = g.M_pad / kTileRows;
+  const int ntiles = (int)(g.M_pad / kTileRows);
+  const int last_valid = (int)(g.M - (int64_t)(ntiles - 1) * kTileRows);  // 1..64
   const int64_t bh_off = ((int64_t)b * g.H + h) * g.M_pad * kHeadDim;
   const u32x4* kc4 = reinterpret_cast<const u32x4*>(Kc + bh_off);
   const u32x4* vc4 = reinterpret_cast<const u32x4*>(Vc + bh_off);
+  auto lds_k = [&](int buf) { return reinterpret_cast<u32x4*>(sK[buf]); };
+  auto lds_v = [&](int buf) { return reinterpret_cast<u32x4*>(sV[buf]); };
 
   // ---- Q fragments (B operand of S^T = K Q^T), pre-multiplied by scale*log2(e) ----
   Frag Qf[2][4];
-  int64_t qrow[2];
-  int64_t qbase[2];
+  bool dropped[2];
+  float l_self[2], l_mean[2];  // base-2 logits of the extras (-inf when absent)
+  const bool use_mean = (flags & AGG_MEAN) && g.n_dropped > 0;
+  const bool use_diag = (flags & AGG_DIAG) && g.n_dropped > 0;
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb) {
-    int64_t q = (int64_t)qt * kQTile + wave * 64 + qb * 32 + l32;
-    qrow[qb] = q;
-    int64_t qc = q < g.NQ ? q : g.NQ - 1;  // tail rows recompute the last query, never stored
-    qbase[qb] = (((int64_t)b * g.NQ + qc) * g.H + h) * kHeadDim;
+    const int64_t q = (int64_t)qt * kQTile + wave * 64 + qb * 32 + l32;
+    const int64_t qc = q < g.NQ ? q : g.NQ - 1;  // tail rows recompute the last query, never stored
+    const int64_t qbase = (((int64_t)b * g.NQ + qc) * g.H + h) * kHeadDim;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      u32x4 raw = *reinterpret_cast<const u32x4*>(Q + qbase[qb] + ks * 16 + g2 * 8);
+      u32x4 raw = *reinterpret_cast<const u32x4*>(Q + qbase + ks * 16 + g2 * 8);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         Qf[qb][ks].u[i] = pack_bf16(bf16_lo(raw[i]) * qscale, bf16_hi(raw[i]) * qscale);
     }
-  }
-
-  // ---- online-softmax state; the extras (self term, mean term) are its initial value ----
-  SoftmaxState st;
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    st.m_ref[qb] = -INFINITY;
-    st.l_part[qb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) st.Oacc[qb][db][r] = 0.f;
-  }
-
-  const bool use_mean = (flags & AGG_MEAN) && g.n_dropped > 0;
-  const bool use_diag = (flags & AGG_DIAG) && g.n_dropped > 0;
-  if (use_mean || use_diag) {
-    const float* km = kmean + ((int64_t)b * g.H + h) * kHeadDim;
-    const float* vm = vmean + ((int64_t)b * g.H + h) * kHeadDim;
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const bool dropped = use_diag && qrow[qb] < g.NQ && token_is_dropped(g, qrow[qb]);
-      float dot_self = 0.f, dot_mean = 0.f;
+    // logits of the extras: lanes l and l^32 hold the two halves of the channel range
+    dropped[qb] = use_diag && q < g.NQ && token_is_dropped(g, q);
+    float dot_self = 0.f, dot_mean = 0.f;
+    if (use_mean || use_diag) {
+      const float* km = kmean + ((int64_t)b * g.H + h) * kHeadDim;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         const int d0 = ks * 16 + g2 * 8;
@@ -267,120 +213,262 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
           qv[2 * i + 1] = bf16_hi(Qf[qb][ks].u[i]);
         }
         if (use_mean) {
-          f32x4 a = *reinterpret_cast<const f32x4*>(km + d0);
-          f32x4 c = *reinterpret_cast<const f32x4*>(km + d0 + 4);
+          f32x4 c0 = *reinterpret_cast<const f32x4*>(km + d0);
+          f32x4 c1 = *reinterpret_cast<const f32x4*>(km + d0 + 4);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) dot_mean += qv[i] * a[i] + qv[4 + i] * c[i];
+          for (int i = 0; i < 4; ++i) dot_mean += qv[i] * c0[i] + qv[4 + i] * c1[i];
         }
-        if (dropped) {
-          u32x4 kr = *reinterpret_cast<const u32x4*>(K + qbase[qb] + d0);
+        if (dropped[qb]) {
+          u32x4 kr = *reinterpret_cast<const u32x4*>(K + qbase + d0);
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             dot_self += qv[2 * i] * bf16_lo(kr[i]) + qv[2 * i + 1] * bf16_hi(kr[i]);
         }
       }
-      // lanes l and l^32 hold the two halves of the channel range
-      dot_self += __shfl_xor(dot_self, 32);
-      dot_mean += __shfl_xor(dot_mean, 32);
-      const float l_self = dropped ? dot_self : -INFINITY;
-      const float l_mean = use_mean ? dot_mean + mean_bias2 : -INFINITY;
-      const float m0 = fmaxf(l_self, l_mean);
+    }
+    dot_self += __shfl_xor(dot_self, 32);
+    dot_mean += __shfl_xor(dot_mean, 32);
+    l_self[qb] = dropped[qb] ? dot_self : -INFINITY;
+    l_mean[qb] = use_mean ? dot_mean + mean_bias2 : -INFINITY;
+  }
+
+  // Initial accumulator = extras weighted by exp2(logit - m0):  O0[d] = w_self v_i[d] + w_mean vmean[d]
+  auto init_extras = [&](int qb, float m0, f32x16 (&Oq)[2], float& lsum) {
+    const float w_self = dropped[qb] ? fast_exp2(l_self[qb] - m0) : 0.f;
+    const float w_mean = use_mean ? fast_exp2(l_mean[qb] - m0) : 0.f;
+    lsum = (g2 == 0) ? (w_self + w_mean) : 0.f;  // lanes l and l^32 split a row's sum
+    const int64_t q = (int64_t)qt * kQTile + wave * 64 + qb * 32 + l32;
+    const int64_t qc = q < g.NQ ? q : g.NQ - 1;
+    const int64_t qbase = (((int64_t)b * g.NQ + qc) * g.H + h) * kHeadDim;
+    const float* vm = vmean + ((int64_t)b * g.H + h) * kHeadDim;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int d0 = 32 * db + 8 * r4 + 4 * g2;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (use_mean) {
+          f32x4 mv = *reinterpret_cast<const f32x4*>(vm + d0);
+          acc = mv * w_mean;
+        }
+        if (dropped[qb]) {
+          u32x2 vr = *reinterpret_cast<const u32x2*>(V + qbase + d0);
+          acc[0] += w_self * bf16_lo(vr[0]);
+          acc[1] += w_self * bf16_hi(vr[0]);
+          acc[2] += w_self * bf16_lo(vr[1]);
+          acc[3] += w_self * bf16_hi(vr[1]);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) Oq[db][r4 * 4 + i] = acc[i];
+      }
+  };
+
+  f32x16 Oacc[2][2];  // [query block][channel block] O^T; channel = 32db + 8(r/4) + 4g2 + r%4
+  float m_fin[2] = {0.f, 0.f};  // reference of the final state (0 on the fast path)
+  float l_fin[2];
+
+  // =============================== fast path ===============================
+  {
+    float la[2][2];  // two partial row sums per query block
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      float l0;
+      init_extras(qb, 0.f, Oacc[qb], l0);
+      la[qb][0] = l0;
+      la[qb][1] = 0.f;
+    }
+
+    // stage tiles 0 and 1; keep tile 2 in registers
+    u32x4 pk0 = kc4[tid], pk1 = kc4[tid + kAttnThreads];
+    u32x4 pv0 = vc4[tid], pv1 = vc4[tid + kAttnThreads];
+    lds_k(0)[tid] = pk0;
+    lds_k(0)[tid + kAttnThreads] = pk1;
+    lds_v(0)[tid] = pv0;
+    lds_v(0)[tid + kAttnThreads] = pv1;
+    if (ntiles > 1) {
+      pk0 = kc4[kChunks + tid];
+      pk1 = kc4[kChunks + tid + kAttnThreads];
+      pv0 = vc4[kChunks + tid];
+      pv1 = vc4[kChunks + tid + kAttnThreads];
+      lds_k(1)[tid] = pk0;
+      lds_k(1)[tid + kAttnThreads] = pk1;
+      lds_v(1)[tid] = pv0;
+      lds_v(1)[tid + kAttnThreads] = pv1;
+    }
+    if (ntiles > 2) {
+      pk0 = kc4[2 * kChunks + tid];
+      pk1 = kc4[2 * kChunks + tid + kAttnThreads];
+      pv0 = vc4[2 * kChunks + tid];
+      pv1 = vc4[2 * kChunks + tid + kAttnThreads];
+    }
+    lds_barrier();
+
+    // pipeline prologue: scores of block 0 and probabilities of its first query block
+    Frag a[4], v[4];
+    Frag P0[2], P1[2];
+    f32x16 S1;
+    {
+      f32x16 S0;
+      load_k_frags(lds_k(0), 0, l32, g2, a);
+      qk8(a, Qf, S0, S1);
+      load_k_frags(lds_k(0), 1, l32, g2, a);
+      exp16(S0, P0, la[0][0], la[0][1]);
+    }
+
+    // invariant at the top of iteration t: a = K fragments of block (t,1); S1 = scores of
+    // block (t,0) for query block 1; P0 = probabilities of block (t,0) for query block 0
+    int cur = 0;  // LDS buffer of tile t
+    for (int t = 0; t + 1 < ntiles; ++t) {
+      const int nxt = (cur == kLdsTiles - 1) ? 0 : cur + 1;
+      const int wrt = (nxt == kLdsTiles - 1) ? 0 : nxt + 1;
+      if (t + 2 < ntiles) {  // tile t+2 -> the buffer tile t-1 has left
+        lds_k(wrt)[tid] = pk0;
+        lds_k(wrt)[tid + kAttnThreads] = pk1;
+        lds_v(wrt)[tid] = pv0;
+        lds_v(wrt)[tid + kAttnThreads] = pv1;
+        if (t + 3 < ntiles) {
+          const int64_t off = (int64_t)(t + 3) * kChunks + tid;
+          pk0 = kc4[off];
+          pk1 = kc4[off + kAttnThreads];
+          pv0 = vc4[off];
+          pv1 = vc4[off + kAttnThreads];
+        }
+      }
+      f32x16 Sn0, Sn1, Sm0;
+      Frag P0b[2];
+      // X(t,0): scores of block (t,1)        | probabilities of block (t,0), query block 1
+      load_v_frags(lds_v(cur), 0, l32, g2, v);
+      qk8(a, Qf, Sn0, Sn1);
+      exp16(S1, P1, la[1][0], la[1][1]);
+      // Y(t,0): P V of block (t,0)           | probabilities of block (t,1), query block 0
+      load_k_frags(lds_k(nxt), 0, l32, g2, a);
+      pv8(v, P0, P1, Oacc);
+      exp16(Sn0, P0b, la[0][0], la[0][1]);
+      // X(t,1): scores of block (t+1,0)      | probabilities of block (t,1), query block 1
+      load_v_frags(lds_v(cur), 1, l32, g2, v);
+      qk8(a, Qf, Sm0, S1);
+      exp16(Sn1, P1, la[1][0], la[1][1]);
+      // Y(t,1): P V of block (t,1)           | probabilities of block (t+1,0), query block 0
+      load_k_frags(lds_k(nxt), 1, l32, g2, a);
+      pv8(v, P0b, P1, Oacc);
+      exp16(Sm0, P0, la[0][0], la[0][1]);
+      lds_barrier();
+      cur = nxt;
+    }
+    {  // last tile: no further scores to start; the only tile with zero-padded rows
+      const int T = ntiles - 1;
+      (void)T;
+      f32x16 Sn0, Sn1;
+      Frag P0b[2];
+      load_v_frags(lds_v(cur), 0, l32, g2, v);
+      qk8(a, Qf, Sn0, Sn1);
+      exp16(S1, P1, la[1][0], la[1][1]);
+      pv8(v, P0, P1, Oacc);
+      exp16(Sn0, P0b, la[0][0], la[0][1]);
+      load_v_frags(lds_v(cur), 1, l32, g2, v);
+      exp16(Sn1, P1, la[1][0], la[1][1]);
+      pv8(v, P0b, P1, Oacc);
+    }
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const float lp = la[qb][0] + la[qb][1];
+      // zero-padded keys have score exactly 0, probability exactly 1 and a zero value row:
+      // they only add their count to the row sum
+      l_fin[qb] = lp + __shfl_xor(lp, 32) - (float)(kTileRows - last_valid);
+    }
+  }
+
+  // A row sum outside [2^-90, 2^90] (or NaN) means the unreferenced exponentials were not
+  // safe for this row: every wavefront of the workgroup then recomputes with running maxima.
+  // (with padded keys the lower bound is 1, so that removing their count loses no precision)
+  const float sum_lo = (last_valid < kTileRows) ? 1.0f : kSumLo;
+  const bool unsafe = !(l_fin[0] < kSumHi) || !(l_fin[0] > sum_lo) || !(l_fin[1] < kSumHi) ||
+                      !(l_fin[1] > sum_lo);
+  if (__syncthreads_or(unsafe ? 1 : 0)) {
+    // ============================= general path =============================
+    float m_run[2], l_part[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const float m0 = fmaxf(l_self[qb], l_mean[qb]);
+      m_run[qb] = m0;
       if (m0 > -INFINITY) {
-        const float w_self = dropped ? fast_exp2(l_self - m0) : 0.f;
-        const float w_mean = use_mean ? fast_exp2(l_mean - m0) : 0.f;
-        st.m_ref[qb] = m0;
-        st.l_part[qb] = (g2 == 0) ? (w_self + w_mean) : 0.f;
+        init_extras(qb, m0, Oacc[qb], l_part[qb]);
+      } else {
+        l_part[qb] = 0.f;
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
-          for (int r4 = 0; r4 < 4; ++r4) {
-            const int d0 = 32 * db + 8 * r4 + 4 * g2;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            if (use_mean) {
-              f32x4 mv = *reinterpret_cast<const f32x4*>(vm + d0);
-              acc = mv * w_mean;
-            }
-            if (dropped) {
-              u32x2 vr = *reinterpret_cast<const u32x2*>(V + qbase[qb] + d0);
-              acc[0] += w_self * bf16_lo(vr[0]);
-              acc[1] += w_self * bf16_hi(vr[0]);
-              acc[2] += w_self * bf16_lo(vr[1]);
-              acc[3] += w_self * bf16_hi(vr[1]);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) st.Oacc[qb][db][r4 * 4 + i] = acc[i];
-          }
+          for (int r = 0; r < 16; ++r) Oacc[qb][db][r] = 0.f;
       }
     }
-  }
+    for (int t = 0; t < ntiles; ++t) {
+      __syncthreads();  // previous tile fully consumed
+      const int64_t off = (int64_t)t * kChunks + tid;
+      lds_k(0)[tid] = kc4[off];
+      lds_k(0)[tid + kAttnThreads] = kc4[off + kAttnThreads];
+      lds_v(0)[tid] = vc4[off];
+      lds_v(0)[tid + kAttnThreads] = vc4[off + kAttnThreads];
+      __syncthreads();
+      const int valid = (t == ntiles - 1) ? last_valid : kTileRows;
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
+      for (int kb = 0; kb < 2; ++kb) {
+        Frag a[4], v[4];
+        load_k_frags(lds_k(0), kb, l32, g2, a);
+        load_v_frags(lds_v(0), kb, l32, g2, v);
+        f32x16 S[2];
+        qk8(a, Qf, S[0], S[1]);
+        Frag P[2][2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) st.negM[qb][r] = -st.m_ref[qb];  // +inf until a reference exists
-
-  // ---- key loop: double-buffered LDS tiles, next tile prefetched into registers ----
-  u32x4 pk0, pk1, pv0, pv1;
-  pk0 = kc4[tid];
-  pk1 = kc4[tid + kAttnThreads];
-  pv0 = vc4[tid];
-  pv1 = vc4[tid + kAttnThreads];
-  {
-    u32x4* dk = reinterpret_cast<u32x4*>(sK[0]);
-    u32x4* dv = reinterpret_cast<u32x4*>(sV[0]);
-    dk[tid] = pk0;
-    dk[tid + kAttnThreads] = pk1;
-    dv[tid] = pv0;
-    dv[tid + kAttnThreads] = pv1;
-  }
-  __syncthreads();
-
-  const int last_valid = (int)(g.M - (ntiles - 1) * kTileRows);  // 1..64
-  for (int64_t t = 0; t + 1 < ntiles; ++t) {
-    const int buf = (int)(t & 1);
-    {
-      const u32x4* nk = kc4 + (t + 1) * (kTileElems / 8);
-      const u32x4* nv = vc4 + (t + 1) * (kTileElems / 8);
-      pk0 = nk[tid];
-      pk1 = nk[tid + kAttnThreads];
-      pv0 = nv[tid];
-      pv1 = nv[tid + kAttnThreads];
+        for (int qb = 0; qb < 2; ++qb) {
+          if (valid < kTileRows) mask16(S[qb], kb, valid, g2);
+          float mx = S[qb][0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[qb][r]);
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          // finite from the first block on: compacted row 0 always exists (block 0 of tile 0)
+          const float m_new = fmaxf(m_run[qb], mx);
+          const float alpha = fast_exp2(m_run[qb] - m_new);  // -inf -> 0
+          m_run[qb] = m_new;
+          float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) S[qb][r] -= m_new;
+          exp16(S[qb], P[qb], rs0, rs1);
+          l_part[qb] = l_part[qb] * alpha + (rs0 + rs1);
+#pragma unroll
+          for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Oacc[qb][db][r] *= alpha;
+        }
+        pv8(v, P[0], P[1], Oacc);
+      }
     }
-    process_tile<false>(reinterpret_cast<const u32x4*>(sK[buf]),
-                        reinterpret_cast<const u32x4*>(sV[buf]), kTileRows, Qf, st, l32, g2);
-    {
-      u32x4* dk = reinterpret_cast<u32x4*>(sK[buf ^ 1]);
-      u32x4* dv = reinterpret_cast<u32x4*>(sV[buf ^ 1]);
-      dk[tid] = pk0;
-      dk[tid + kAttnThreads] = pk1;
-      dv[tid] = pv0;
-      dv[tid + kAttnThreads] = pv1;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      m_fin[qb] = m_run[qb];
+      l_fin[qb] = l_part[qb] + __shfl_xor(l_part[qb], 32);
     }
-    __syncthreads();
-  }
-  {  // last tile, outside the loop: the only one that can hold zero-padded rows
-    const int buf = (int)((ntiles - 1) & 1);
-    process_tile<true>(reinterpret_cast<const u32x4*>(sK[buf]),
-                       reinterpret_cast<const u32x4*>(sV[buf]), last_valid, Qf, st, l32, g2);
   }
 
   // ---- normalise and store ----
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb) {
-    const float l = st.l_part[qb] + __shfl_xor(st.l_part[qb], 32);
+    const float l = l_fin[qb];
     const float inv = 1.0f / l;
-    if (qrow[qb] < g.NQ) {
+    const int64_t q = (int64_t)qt * kQTile + wave * 64 + qb * 32 + l32;
+    if (q < g.NQ) {
+      const int64_t qbase = (((int64_t)b * g.NQ + q) * g.H + h) * kHeadDim;
 #pragma unroll
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
           const int d0 = 32 * db + 8 * r4 + 4 * g2;
           u32x2 w;
-          w[0] = pack_bf16(st.Oacc[qb][db][r4 * 4 + 0] * inv, st.Oacc[qb][db][r4 * 4 + 1] * inv);
-          w[1] = pack_bf16(st.Oacc[qb][db][r4 * 4 + 2] * inv, st.Oacc[qb][db][r4 * 4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(O + qbase[qb] + d0) = w;
+          w[0] = pack_bf16(Oacc[qb][db][r4 * 4 + 0] * inv, Oacc[qb][db][r4 * 4 + 1] * inv);
+          w[1] = pack_bf16(Oacc[qb][db][r4 * 4 + 2] * inv, Oacc[qb][db][r4 * 4 + 3] * inv);
+          *reinterpret_cast<u32x2*>(O + qbase + d0) = w;
         }
       if (lse && g2 == 0)
-        lse[((int64_t)b * g.H + h) * g.NQ + qrow[qb]] = (st.m_ref[qb] + log2f(l)) * kLn2;
+        lse[((int64_t)b * g.H + h) * g.NQ + q] = (m_fin[qb] + log2f(l)) * kLn2;
     }
   }
 }
