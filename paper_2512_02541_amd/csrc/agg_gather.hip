@@ -87,17 +87,25 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(Geom g, const ui
 }
 
 // ---------------------------------------------------------------------------
-// Mean component.  Stage 1: each workgroup sums kMeanRows consecutive dropped
+// Mean component.  Stage 1: each workgroup sums a run of consecutive dropped
 // rows (all H*64 channels of K and of V) in a fixed order and writes one
-// partial.  Stage 2: one thread per channel adds the partials in order, in
-// double, and divides by the number of dropped patches.  No atomics: the
-// result is bit-reproducible.
+// partial.  Stage 2: the partials are added in a fixed order, in double, and
+// divided by the number of dropped patches.  No atomics: the result is
+// bit-reproducible.
 // ---------------------------------------------------------------------------
 constexpr int kMeanThreads = 256;
-constexpr int kMeanRows = 256;  // dropped rows per partial
+constexpr int kMeanBatch = 256;       // token ids resolved per pass through LDS
+constexpr int kMeanMaxChunks = 4096;  // upper bound on partials per batch element
+
+// dropped rows per partial: at least 32, and few enough partials for a cheap second stage
+static int mean_rows_per_chunk(const Geom& g) {
+  int64_t rows = (g.n_dropped + kMeanMaxChunks - 1) / kMeanMaxChunks;
+  return (int)(rows < 32 ? 32 : rows);
+}
 
 int mean_chunks(const Geom& g) {
-  return (int)((g.n_dropped + kMeanRows - 1) / kMeanRows);
+  const int rows = mean_rows_per_chunk(g);
+  return (int)((g.n_dropped + rows - 1) / rows);
 }
 
 __device__ inline void add_bf16x8(float (&acc)[8], const u32x4& v) {
@@ -108,14 +116,16 @@ __device__ inline void add_bf16x8(float (&acc)[8], const u32x4& v) {
   }
 }
 
-// Threads are laid out as (row lane, 16-byte chunk of the row): cpr chunks per
-// row, rpp rows in flight per pass.  Channel block blockIdx.y covers chunks
-// [256*y, 256*y + cpr_b).
-__global__ __launch_bounds__(kMeanThreads) void mean_partial_kernel(Geom g, const uint16_t* __restrict__ K,
-                                                                    const uint16_t* __restrict__ V,
-                                                                    float* __restrict__ partial,
-                                                                    int nchunks, int cpr_b, int rpp) {
+// Threads are laid out as (row lane, 16-byte chunk of the row): cpr_b chunks per row, rpp
+// rows in flight per pass.  Channel block blockIdx.y covers chunks [256*y, 256*y + cpr_b).
+// Token ids of the run are resolved kMeanBatch at a time into LDS (one integer division
+// chain per row instead of one per load), and four rows per lane are requested before any
+// is added, so that enough bytes are in flight to cover HBM latency.
+__global__ __launch_bounds__(kMeanThreads) void mean_partial_kernel(
+    Geom g, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    float* __restrict__ partial, int nchunks, int rows_per_chunk, int cpr_b, int rpp) {
   __shared__ float red[kMeanThreads][17];
+  __shared__ int32_t sTok[kMeanBatch];
   const int tid = threadIdx.x;
   const int chunk = blockIdx.x;
   const int b = blockIdx.z;
@@ -124,21 +134,43 @@ __global__ __launch_bounds__(kMeanThreads) void mean_partial_kernel(Geom g, cons
   const int rl = tid / cpr_b;             // row lane
   const int col = (blockIdx.y * kMeanThreads + cg) * 8;  // first channel of this thread
   const bool active = (rl < rpp) && (col < C);
+  const uint16_t* Kb = K + (int64_t)b * g.NQ * C + col;
+  const uint16_t* Vb = V + (int64_t)b * g.NQ * C + col;
 
   float ak[8], av[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) ak[i] = av[i] = 0.f;
 
-  const int64_t u0 = (int64_t)chunk * kMeanRows;
-  const int64_t u1 = min(u0 + kMeanRows, g.n_dropped);
-  if (active) {
-    for (int64_t u = u0 + rl; u < u1; u += rpp) {
-      int64_t tok = dropped_to_token(g, u);
-      int64_t off = ((int64_t)b * g.NQ + tok) * C + col;
-      u32x4 kv = *reinterpret_cast<const u32x4*>(K + off);
-      u32x4 vv = *reinterpret_cast<const u32x4*>(V + off);
-      add_bf16x8(ak, kv);
-      add_bf16x8(av, vv);
+  const int64_t u0 = (int64_t)chunk * rows_per_chunk;
+  const int64_t u1 = min(u0 + rows_per_chunk, g.n_dropped);
+  for (int64_t base = u0; base < u1; base += kMeanBatch) {
+    const int n = (int)min((int64_t)kMeanBatch, u1 - base);
+    __syncthreads();  // previous batch consumed
+    if (tid < n) sTok[tid] = (int32_t)dropped_to_token(g, base + tid);
+    __syncthreads();
+    if (active) {
+      int r = rl;
+      for (; r + 3 * rpp < n; r += 4 * rpp) {
+        u32x4 kv[4], vv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t off = (int64_t)sTok[r + j * rpp] * C;
+          kv[j] = *reinterpret_cast<const u32x4*>(Kb + off);
+          vv[j] = *reinterpret_cast<const u32x4*>(Vb + off);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          add_bf16x8(ak, kv[j]);
+          add_bf16x8(av, vv[j]);
+        }
+      }
+      for (; r < n; r += rpp) {
+        const int64_t off = (int64_t)sTok[r] * C;
+        u32x4 kv = *reinterpret_cast<const u32x4*>(Kb + off);
+        u32x4 vv = *reinterpret_cast<const u32x4*>(Vb + off);
+        add_bf16x8(ak, kv);
+        add_bf16x8(av, vv);
+      }
     }
   }
   // combine the row lanes in ascending order (fixed order -> reproducible)
@@ -170,19 +202,35 @@ __global__ __launch_bounds__(kMeanThreads) void mean_partial_kernel(Geom g, cons
   }
 }
 
-__global__ __launch_bounds__(256) void mean_final_kernel(Geom g, const float* __restrict__ partial,
-                                                         int nchunks, float* __restrict__ kmean,
-                                                         float* __restrict__ vmean) {
+// Second stage: a workgroup owns 32 consecutive channels (of K or of V); its 8 row groups
+// each add every 8th partial in double, then the 8 sums are added in order.
+constexpr int kFinalCols = 32;
+constexpr int kFinalGroups = 8;
+__global__ __launch_bounds__(kFinalCols * kFinalGroups) void mean_final_kernel(
+    Geom g, const float* __restrict__ partial, int nchunks, float* __restrict__ kmean,
+    float* __restrict__ vmean) {
+  __shared__ double red[kFinalGroups][kFinalCols];
   const int C = g.H * kHeadDim;
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;  // 0 .. 2C-1 : K channels then V channels
+  const int cl = threadIdx.x % kFinalCols;
+  const int rg = threadIdx.x / kFinalCols;
+  const int c = blockIdx.x * kFinalCols + cl;  // 0 .. 2C-1 : K channels then V channels
   const int b = blockIdx.y;
-  if (c >= 2 * C) return;
-  const int which = c / C, col = c % C;
   double s = 0.0;
-  for (int k = 0; k < nchunks; ++k)
-    s += (double)partial[(((int64_t)b * nchunks + k) * 2 + which) * C + col];
-  float m = (g.n_dropped > 0) ? (float)(s / (double)g.n_dropped) : 0.f;
-  (which ? vmean : kmean)[(int64_t)b * C + col] = m;
+  if (c < 2 * C) {
+    const int which = c / C, col = c % C;
+    const float* p = partial + ((int64_t)b * nchunks * 2 + which) * C + col;
+#pragma unroll 8
+    for (int k = rg; k < nchunks; k += kFinalGroups) s += (double)p[(int64_t)k * 2 * C];
+  }
+  red[rg][cl] = s;
+  __syncthreads();
+  if (rg == 0 && c < 2 * C) {
+    double t = 0.0;
+    for (int r = 0; r < kFinalGroups; ++r) t += red[r][cl];
+    const float m = (g.n_dropped > 0) ? (float)(t / (double)g.n_dropped) : 0.f;
+    const int which = c / C, col = c % C;
+    (which ? vmean : kmean)[(int64_t)b * C + col] = m;
+  }
 }
 
 hipError_t launch_gather(const Geom& g, const void* K, const void* V, void* Kc, void* Vc,
@@ -205,15 +253,16 @@ hipError_t launch_mean(const Geom& g, const void* K, const void* V, float* kmean
     const int rpp = kMeanThreads / cpr_b;
     dim3 grid((unsigned)nchunks, (unsigned)((cpr + kMeanThreads - 1) / kMeanThreads), (unsigned)g.B);
     (void)hipGetLastError();  // drop any stale error so the check below is this launch's
-  hipLaunchKernelGGL(mean_partial_kernel, grid, dim3(kMeanThreads), 0, st, g, (const uint16_t*)K,
-                       (const uint16_t*)V, (float*)workspace, nchunks, cpr_b, rpp);
+    hipLaunchKernelGGL(mean_partial_kernel, grid, dim3(kMeanThreads), 0, st, g, (const uint16_t*)K,
+                       (const uint16_t*)V, (float*)workspace, nchunks, mean_rows_per_chunk(g), cpr_b,
+                       rpp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  dim3 grid2((unsigned)((2 * C + 255) / 256), (unsigned)g.B);
+  dim3 grid2((unsigned)((2 * C + kFinalCols - 1) / kFinalCols), (unsigned)g.B);
   (void)hipGetLastError();  // drop any stale error so the check below is this launch's
-  hipLaunchKernelGGL(mean_final_kernel, grid2, dim3(256), 0, st, g, (const float*)workspace, nchunks,
-                     kmean, vmean);
+  hipLaunchKernelGGL(mean_final_kernel, grid2, dim3(kFinalCols * kFinalGroups), 0, st, g,
+                     (const float*)workspace, nchunks, kmean, vmean);
   return hipGetLastError();
 }
 

@@ -34,14 +34,16 @@ struct Geom {
 __host__ __device__ inline int64_t kept_row_to_token(const Geom& g, int64_t m) {
   int64_t frame;
   int32_t j;
+  // m < M <= N*L < 2^31: 32-bit division (much cheaper on the GPU than 64-bit)
   if (g.keep_first) {
     if (m < g.L) return m;
-    int64_t r = m - g.L;
-    frame = 1 + r / g.rows_sub;
-    j = (int32_t)(r % g.rows_sub);
+    const uint32_t r = (uint32_t)(m - g.L);
+    frame = 1 + (int64_t)(r / (uint32_t)g.rows_sub);
+    j = (int32_t)(r % (uint32_t)g.rows_sub);
   } else {
-    frame = m / g.rows_sub;
-    j = (int32_t)(m % g.rows_sub);
+    const uint32_t r = (uint32_t)m;
+    frame = (int64_t)(r / (uint32_t)g.rows_sub);
+    j = (int32_t)(r % (uint32_t)g.rows_sub);
   }
   int32_t slot;
   if (j < g.P) {
@@ -59,8 +61,10 @@ __host__ __device__ inline int64_t kept_row_to_token(const Geom& g, int64_t m) {
 // A grid row r with r % s_h != 0 is dropped entirely (n_w patches); a row with
 // r % s_h == 0 drops the columns c with c % s_w != 0 (dw patches).
 __host__ __device__ inline int64_t dropped_to_token(const Geom& g, int64_t u) {
-  int64_t frame = (g.keep_first ? 1 : 0) + u / g.df;
-  int32_t j = (int32_t)(u % g.df);
+  // u < n_dropped <= N*L < 2^31: 32-bit division (much cheaper on the GPU than 64-bit)
+  const uint32_t uu = (uint32_t)u;
+  int64_t frame = (g.keep_first ? 1 : 0) + (int64_t)(uu / (uint32_t)g.df);
+  int32_t j = (int32_t)(uu % (uint32_t)g.df);
   // rows come in groups of s_h: the first keeps some columns, the rest are dropped whole
   int32_t per_group = g.dw + (g.s_h - 1) * g.n_w;  // > 0 whenever anything is dropped
   if (per_group < 1) per_group = 1;
