@@ -107,7 +107,15 @@ def run_workload(name, steps, warmup, dense, log):
         res.update({"ms_dense": ms_dense, "tflops_dense": dflops / (ms_dense * 1e-3) / 1e12,
                     "speedup_vs_dense": ms_dense / ms_step,
                     "ideal_speedup": w.NQ / buf.M})
-        del ws, Od
+        del ws
+        # frame attention (Global-to-Frame conversion of an early global block), same tensors
+        nwf = agg.agg_frame_workspace_bytes(shape)
+        wf = torch.empty(nwf, dtype=torch.uint8, device="cuda")
+        ms_frame, _ = time_events(
+            lambda: agg.agg_frame_attn_fwd(shape, q, k, v, Od, None, wf, nwf), max(1, min(steps, 3)), 1)
+        fflops = 4.0 * w.N * w.L * w.L * w.D * w.H
+        res.update({"ms_frame_attn": ms_frame, "tflops_frame_attn": fflops / (ms_frame * 1e-3) / 1e12})
+        del wf, Od
     return res, (w, shape, q, k, v, buf)
 
 
@@ -270,6 +278,8 @@ def main():
                    "gather_gbs": res["gather_gbs"], "gather_frac_hbm": res["gather_frac_hbm"],
                    "frac_bf16_peak_layer": res["tflops_layer"] / PEAK_BF16_TFLOPS,
                    "ms_dense": res.get("ms_dense"), "tflops_dense": res.get("tflops_dense"),
+                   "ms_frame_attn": res.get("ms_frame_attn"),
+                   "tflops_frame_attn": res.get("tflops_frame_attn"),
                    "speedup_vs_dense": res.get("speedup_vs_dense"),
                    "ideal_speedup": res.get("ideal_speedup"),
                    "paper_context": "end-to-end speedups ~2x/4-5x/8-10x at 100/300/800 frames on "

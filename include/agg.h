@@ -142,6 +142,17 @@ int agg_dense_global_attn_fwd(const agg_shape* shape, const void* Q, const void*
                               void* O, float* lse, void* workspace, size_t workspace_bytes,
                               void* hip_stream);
 
+/*
+ * Sec. 4.2, Global-to-Frame conversion: attention applied independently inside every frame,
+ * i.e. on the (B*N, L, C) layout -- what an early global block becomes when its rearrangement
+ * to (B, N*L, C) is skipped.  Q, K, V, O: the same device tensors as above (a frame's tokens are
+ * contiguous in them).  lse: device float32 [B*N, H, L] or NULL.  shape->s_h, s_w, flags and
+ * keep_first_frame are ignored.  workspace: device, >= agg_frame_workspace_bytes().
+ */
+size_t agg_frame_workspace_bytes(const agg_shape* shape);
+int agg_frame_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V, void* O,
+                       float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -313,3 +313,52 @@ void osga_dense_rows(const osga_shape* s, const uint16_t* Q, const uint16_t* K, 
     free(q);
   }
 }
+
+/* Frame attention (Sec. 4.2, Global-to-Frame conversion): the rearrangement to the
+ * (B, N*L, C) layout is skipped, so a query only sees the tokens of its own frame.
+ * rows are token ids of the sequence; lse is [B, H, nrows]. */
+void osga_frame_rows(const osga_shape* s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
+                     const int64_t* rows, int64_t nrows, double* O, double* lse) {
+  int64_t L = tokens_per_frame(s);
+  int64_t NQ = (int64_t)s->N * L;
+  int64_t H = s->H, D = s->D;
+  int64_t work = (int64_t)s->B * nrows * H;
+#pragma omp parallel
+  {
+    double* logit = (double*)malloc((size_t)L * sizeof(double));
+    double* q = (double*)malloc((size_t)D * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t w = 0; w < work; ++w) {
+      int64_t b = w / (nrows * H);
+      int64_t r = (w / H) % nrows;
+      int64_t h = w % H;
+      int64_t i = rows[r];
+      int64_t first = (i / L) * L; /* first token of the query's frame */
+      const uint16_t* qr = Q + ((b * NQ + i) * H + h) * D;
+      for (int64_t d = 0; d < D; ++d) q[d] = bf16_to_double(qr[d]);
+      double mx = -INFINITY;
+      for (int64_t j = 0; j < L; ++j) {
+        const uint16_t* kr = K + ((b * NQ + first + j) * H + h) * D;
+        double acc = 0.0;
+        for (int64_t d = 0; d < D; ++d) acc += q[d] * bf16_to_double(kr[d]);
+        logit[j] = (double)s->scale * acc;
+        if (logit[j] > mx) mx = logit[j];
+      }
+      double denom = 0.0;
+      for (int64_t j = 0; j < L; ++j) {
+        logit[j] = exp(logit[j] - mx);
+        denom += logit[j];
+      }
+      double* o = O + ((b * nrows + r) * H + h) * D;
+      for (int64_t d = 0; d < D; ++d) o[d] = 0.0;
+      for (int64_t j = 0; j < L; ++j) {
+        const uint16_t* vr = V + ((b * NQ + first + j) * H + h) * D;
+        double p = logit[j] / denom;
+        for (int64_t d = 0; d < D; ++d) o[d] += p * bf16_to_double(vr[d]);
+      }
+      if (lse) lse[(b * H + h) * nrows + r] = mx + log(denom);
+    }
+    free(logit);
+    free(q);
+  }
+}

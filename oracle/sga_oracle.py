@@ -200,3 +200,16 @@ def sga(shape: Shape, Q, K, V, rows=None, want_p: bool = False):
     O, lse, P = attn_rows(shape, Q, K, V, Kc, Vc, km, vm, n_dropped, rows, want_p)
     return dict(idx=idx, n_dropped=n_dropped, Kc=Kc, Vc=Vc, kmean=km, vmean=vm,
                 O=O, lse=lse, P=P, rows=np.asarray(rows))
+
+
+def frame_rows(shape: Shape, Q, K, V, rows):
+    """Frame attention (Sec. 4.2): each listed query against the tokens of its own frame."""
+    Q, K, V = _u16(Q), _u16(K), _u16(V)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    nrows = int(rows.shape[0])
+    O = np.empty((shape.B, nrows, shape.H, shape.D), dtype=np.float64)
+    lse = np.empty((shape.B, shape.H, nrows), dtype=np.float64)
+    cs = shape.c()
+    lib().osga_frame_rows(ctypes.byref(cs), _p(Q), _p(K), _p(V), _p(rows), ctypes.c_int64(nrows),
+                          _p(O), _p(lse))
+    return O, lse

@@ -60,7 +60,7 @@ EXPORTS = [
     "agg_status_string", "agg_sigma_to_strides", "agg_kv_count", "agg_kv_indices_host",
     "agg_dropped_indices_host", "agg_kv_compact_bytes", "agg_kc_offset", "agg_vc_offset", "agg_workspace_bytes",
     "agg_dense_workspace_bytes", "agg_kv_subsample", "agg_global_attn_fwd",
-    "agg_dense_global_attn_fwd",
+    "agg_dense_global_attn_fwd", "agg_frame_workspace_bytes", "agg_frame_attn_fwd",
 ]
 
 
@@ -98,6 +98,9 @@ def lib():
     L.agg_kv_subsample.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.agg_global_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.agg_dense_global_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.agg_frame_workspace_bytes.restype = ctypes.c_size_t
+    L.agg_frame_workspace_bytes.argtypes = [shp]
+    L.agg_frame_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     _lib = L
     return L
 
@@ -203,3 +206,13 @@ def agg_dense_global_attn_fwd(shape, Q, K, V, O, lse, workspace, workspace_bytes
     _check(lib().agg_dense_global_attn_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
                                            _ptr(lse), _ptr(workspace), int(workspace_bytes),
                                            _stream(stream)), "agg_dense_global_attn_fwd")
+
+
+def agg_frame_workspace_bytes(shape: agg_shape) -> int:
+    return int(lib().agg_frame_workspace_bytes(ctypes.byref(shape)))
+
+
+def agg_frame_attn_fwd(shape, Q, K, V, O, lse, workspace, workspace_bytes, stream=None):
+    _check(lib().agg_frame_attn_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
+                                    _ptr(lse), _ptr(workspace), int(workspace_bytes),
+                                    _stream(stream)), "agg_frame_attn_fwd")

@@ -205,4 +205,30 @@ int agg_dense_global_attn_fwd(const agg_shape* shape, const void* Q, const void*
   return AGG_OK;
 }
 
+// Frame attention is ordinary attention over B*N independent sequences of one frame each:
+// the token-major tensors already hold a frame's L tokens contiguously.
+static int frame_shape(const agg_shape* shape, agg_shape* per_frame) {
+  if (!shape) return AGG_ERR_NULL;
+  if (shape->B < 1 || shape->N < 1) return AGG_ERR_SHAPE;
+  if ((int64_t)shape->B * shape->N > INT32_MAX) return AGG_ERR_OVERFLOW;
+  *per_frame = *shape;
+  per_frame->B = shape->B * shape->N;
+  per_frame->N = 1;
+  return AGG_OK;
+}
+
+size_t agg_frame_workspace_bytes(const agg_shape* shape) {
+  agg_shape f;
+  if (frame_shape(shape, &f) != AGG_OK) return 0;
+  return agg_dense_workspace_bytes(&f);
+}
+
+int agg_frame_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V, void* O,
+                       float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  agg_shape f;
+  int rc = frame_shape(shape, &f);
+  if (rc != AGG_OK) return rc;
+  return agg_dense_global_attn_fwd(&f, Q, K, V, O, lse, workspace, workspace_bytes, hip_stream);
+}
+
 }  // extern "C"

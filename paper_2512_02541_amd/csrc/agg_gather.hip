@@ -202,10 +202,10 @@ __global__ __launch_bounds__(kMeanThreads) void mean_partial_kernel(
   }
 }
 
-// Second stage: a workgroup owns 32 consecutive channels (of K or of V); its 8 row groups
-// each add every 8th partial in double, then the 8 sums are added in order.
+// Second stage: a workgroup owns 32 consecutive channels (of K or of V); its 32 row groups
+// each add every 32nd partial in double, then the 32 sums are added in order.
 constexpr int kFinalCols = 32;
-constexpr int kFinalGroups = 8;
+constexpr int kFinalGroups = 32;
 __global__ __launch_bounds__(kFinalCols * kFinalGroups) void mean_final_kernel(
     Geom g, const float* __restrict__ partial, int nchunks, float* __restrict__ kmean,
     float* __restrict__ vmean) {

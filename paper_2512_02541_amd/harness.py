@@ -90,6 +90,17 @@ def dense_forward(shape, Q, K, V, with_lse=True):
     return O, lse
 
 
+def frame_forward(shape, Q, K, V, with_lse=True):
+    """Per-frame attention (Global-to-Frame conversion); lse comes back as [B*N, H, L]."""
+    B, N, H, D, NQ = shape.B, shape.N, shape.H, shape.D, shape.NQ
+    O = torch.empty((B, NQ, H, D), dtype=torch.bfloat16, device=Q.device)
+    lse = torch.empty((B * N, H, shape.L), dtype=torch.float32, device=Q.device) if with_lse else None
+    nws = agg.agg_frame_workspace_bytes(shape)
+    ws = torch.empty(nws, dtype=torch.uint8, device=Q.device)
+    agg.agg_frame_attn_fwd(shape, Q, K, V, O, lse, ws, nws)
+    return O, lse
+
+
 def decode_compact(flat: torch.Tensor, B: int, H: int, M: int, M_pad: int, which: str) -> torch.Tensor:
     """Fragment-order Kc ('k') or Vc ('v') -> plain [B, H, M_pad, 64] (layout of agg.h)."""
     nt = M_pad // 64

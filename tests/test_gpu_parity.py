@@ -266,3 +266,66 @@ def test_full_size_dense_baseline():
     qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
     want_o, want_lse = orc.dense_rows(oshape(shape), qb, kb, vb, rows)
     check_output(O, lse, want_o, want_lse, rows, "dense f100")
+
+
+# ----------------------------------------------------------------------------
+# Frame attention (Global-to-Frame conversion of early global blocks)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("case", [(2, 3, 5, 7, 2, 3), (1, 4, 16, 16, 5, 16), (1, 2, 37, 37, 5, 2)])
+def test_frame_attention(case):
+    B, N, n_h, n_w, P, H = case
+    shape = agg.make_shape(B, N, n_h, n_w, P, H, 64, 2, 2, 1)
+    q, k, v = inputs.iid_qkv(B, shape.NQ, H, 64, seed=900 + N + H, device="cuda")
+    O, lse = harness.frame_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    rows = np.arange(shape.NQ, dtype=np.int64)
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    want_o, want_lse = orc.frame_rows(oshape(shape), qb, kb, vb, rows)
+    # library lse is [B*N, H, L]; the oracle's is [B, H, N*L]
+    L = shape.L
+    got_lse = lse.view(B, N, H, L).permute(0, 2, 1, 3).reshape(B, H, N * L)
+    check_output(O, got_lse, want_o, want_lse, rows, "frame attention")
+
+
+def test_full_size_frame_attention():
+    w = inputs.WORKLOADS["f100"]
+    q, k, v = inputs.make_qkv(w, "cuda")
+    shape = harness.shape_of(w)
+    O, _ = harness.frame_forward(shape, q, k, v, with_lse=False)
+    torch.cuda.synchronize()
+    rows = sample_rows(w)[:: 3]
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    want_o, _ = orc.frame_rows(oshape(shape), qb, kb, vb, rows)
+    check_output(O, None, want_o, None, rows, "frame f100")
+
+
+# ----------------------------------------------------------------------------
+# The calls only enqueue kernels (no allocation, no synchronisation, no memset), so a
+# layer can be captured into a HIP graph; every replay must reproduce the eager result.
+# ----------------------------------------------------------------------------
+def test_hip_graph_replays_match_eager(tiny_qkv):
+    w, (q, k, v) = tiny_qkv
+    shape = harness.shape_of(w)
+    eager = harness.sga_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    buf = harness.alloc(shape, "cuda", poison=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # warm-up on the capture stream
+        harness.subsample(buf, k, v)
+        harness.attend(buf, q, k, v)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        harness.subsample(buf, k, v)
+        harness.attend(buf, q, k, v)
+    for replay in range(3):
+        for t in (buf.O, buf.Kc, buf.Vc, buf.kmean, buf.vmean):
+            t.fill_(float("nan"))   # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf.O.view(torch.int16), eager.O.view(torch.int16)), replay
+        assert torch.equal(buf.lse, eager.lse), replay
+        assert torch.equal(buf.kmean, eager.kmean) and torch.equal(buf.idx, eager.idx)

@@ -482,3 +482,31 @@ def test_pins_discriminate_planted_mistakes(mistake):
     p = e / e.sum(axis=1, keepdims=True)
     wrong_o = p @ v_aug
     assert np.abs(wrong_o - res["O"][b, :, h]).max() > 1e-4
+
+
+# ----------------------------------------------------------------------------
+# frame attention (Sec. 4.2): block-diagonal dense attention
+# ----------------------------------------------------------------------------
+def test_frame_attention_is_block_diagonal_dense_attention():
+    shape = small_shape(B=2, N=3, flags=0)
+    q, k, v = draw(shape, seed=111)
+    rows = np.arange(shape.NQ)
+    O, lse = orc.frame_rows(shape, bits(q), bits(k), bits(v), rows)
+    qd, kd, vd = (t.to(torch.float64).numpy() for t in (q, k, v))
+    L = shape.L
+    frame_of = np.arange(shape.NQ) // L
+    for b in range(shape.B):
+        for h in range(shape.H):
+            logits = shape.scale * qd[b, :, h] @ kd[b, :, h].T
+            logits = np.where(frame_of[:, None] == frame_of[None, :], logits, -np.inf)
+            mx = logits.max(axis=1, keepdims=True)
+            e = np.exp(logits - mx)
+            den = e.sum(axis=1, keepdims=True)
+            assert np.abs(O[b, :, h] - (e / den) @ vd[b, :, h]).max() < 1e-12
+            assert np.abs(lse[b, h] - (mx + np.log(den))[:, 0]).max() < 1e-12
+    # one frame: frame attention is global attention
+    one = small_shape(N=1, flags=0)
+    q, k, v = draw(one, seed=112)
+    Of, _ = orc.frame_rows(one, bits(q), bits(k), bits(v), np.arange(one.NQ))
+    Od, _ = orc.dense_rows(one, bits(q), bits(k), bits(v), np.arange(one.NQ))
+    assert np.abs(Of - Od).max() == 0.0
