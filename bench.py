@@ -213,6 +213,37 @@ def run_only(args, log):
     return 0
 
 
+def run_sweep(args, log):
+    """Variant sweep of Sec. 4.3 and its ablations on one workload's tensors: every sigma of the
+    paper's table, VGGT (first frame kept) and pi^3 (all frames subsampled) rules, and the
+    SubsampleOnly / WithDiagonal / WithMean / both flag combinations."""
+    import torch
+
+    from paper_2512_02541_amd import binding as agg
+    from paper_2512_02541_amd import harness, inputs
+
+    w = inputs.WORKLOADS[args.workload]
+    q, k, v = inputs.make_qkv(w, "cuda")
+    rows = []
+    cases = [(sig, 1, 3) for sig in (2, 4, 6, 9)] + [(sig, 0, 3) for sig in (2, 4, 6, 9)] + \
+            [(w.s_h * w.s_w, 1, fl) for fl in (0, 1, 2)]
+    for sigma, keep_first, flags in cases:
+        s_h, s_w = agg.agg_sigma_to_strides(sigma)
+        shape = harness.shape_of(w, flags=flags, s_h=s_h, s_w=s_w, keep_first_frame=keep_first)
+        buf = harness.alloc(shape, "cuda", with_lse=False)
+        ms_g, _ = time_events(lambda: harness.subsample(buf, k, v), args.steps, 1)
+        ms_a, _ = time_events(lambda: harness.attend(buf, q, k, v), args.steps, 1)
+        fl_ = sga_flops(w.NQ, buf.M, w.H, w.D)
+        rows.append({"sigma": sigma, "keep_first_frame": keep_first, "flags": flags, "M": buf.M,
+                     "ms_gather": ms_g, "ms_attn": ms_a, "tflops_attn": fl_ / (ms_a * 1e-3) / 1e12})
+        log("sigma %d keep_first %d flags %d: M %d gather %.3f ms attn %.2f ms" % (
+            sigma, keep_first, flags, buf.M, ms_g, ms_a))
+        del buf
+        torch.cuda.empty_cache()
+    print(json.dumps({"sweep": args.workload, "NQ": w.NQ, "rows": rows}))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,6 +255,9 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=384)
+    ap.add_argument("--sweep", action="store_true",
+                    help="time the method's variants on --workload (sigma 2/4/6/9, both first-frame "
+                         "rules, the four diag/mean flag combinations) and print one JSON line")
     ap.add_argument("--only", choices=["attn", "gather", "dense", "copy"], default=None,
                     help="profiling aid: launch just this piece `steps` times (for rocprofv3 runs)")
     args = ap.parse_args()
@@ -246,6 +280,8 @@ def main():
 
     if args.only:
         return run_only(args, log)
+    if args.sweep:
+        return run_sweep(args, log)
 
     res, ctx = run_workload(args.workload, args.steps, args.warmup, not args.no_dense, log)
     cpu, parity = (None, None)
