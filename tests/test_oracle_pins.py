@@ -44,8 +44,7 @@ def bits(t):
 
 # ----------------------------------------------------------------------------
 # A second, independent statement of the kept set: enumerate windows, mark the
-# first token of each (Sec. 4.3, "retain the first patch token within each
-# s_h x s_w window").
+# first token of each (Sec. 4.3: the first patch token of every s_h x s_w window is kept).
 # ----------------------------------------------------------------------------
 def kept_mask_by_windows(shape):
     L = shape.L
