@@ -159,8 +159,8 @@ int agg_kv_subsample(const agg_shape* shape, const void* K, const void* V, void*
     return AGG_ERR_ALIGN;
   if (workspace_bytes < agg_workspace_bytes(shape)) return AGG_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (launch_gather(g, K, V, Kc, Vc, idx, st) != hipSuccess) return AGG_ERR_LAUNCH;
-  if (launch_mean(g, K, V, kmean, vmean, workspace, st) != hipSuccess) return AGG_ERR_LAUNCH;
+  if (launch_subsample(g, K, V, Kc, Vc, idx, kmean, vmean, workspace, st) != hipSuccess)
+    return AGG_ERR_LAUNCH;
   return AGG_OK;
 }
 
@@ -198,7 +198,8 @@ int agg_dense_global_attn_fwd(const agg_shape* shape, const void* Q, const void*
   void* Kf = workspace;
   void* Vf = (char*)workspace + one;
   // repack every row (nothing dropped), then the same attention kernel with no extras
-  if (launch_gather(g, K, V, Kf, Vf, nullptr, st) != hipSuccess) return AGG_ERR_LAUNCH;
+  if (launch_subsample(g, K, V, Kf, Vf, nullptr, nullptr, nullptr, nullptr, st) != hipSuccess)
+    return AGG_ERR_LAUNCH;
   if (launch_attn(g, 0u, shape->scale, 0.0f, Q, K, V, Kf, Vf, nullptr, nullptr, O, lse, st) !=
       hipSuccess)
     return AGG_ERR_LAUNCH;

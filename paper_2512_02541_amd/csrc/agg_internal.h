@@ -114,10 +114,10 @@ __host__ __device__ inline int64_t vc_offset(int64_t m, int32_t d) {
 int make_geom(const agg_shape* s, Geom* g, bool dense);
 
 // Kernel launchers (each returns hipGetLastError() of its launches).
-hipError_t launch_gather(const Geom& g, const void* K, const void* V, void* Kc, void* Vc,
-                         int32_t* idx, hipStream_t st);
-hipError_t launch_mean(const Geom& g, const void* K, const void* V, float* kmean, float* vmean,
-                       void* workspace, hipStream_t st);
+// gather + index list, and (when kmean/vmean are non-null) the mean terms
+hipError_t launch_subsample(const Geom& g, const void* K, const void* V, void* Kc, void* Vc,
+                            int32_t* idx, float* kmean, float* vmean, void* workspace,
+                            hipStream_t st);
 hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bias, const void* Q,
                        const void* K, const void* V, const void* Kc, const void* Vc,
                        const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st);
