@@ -153,6 +153,37 @@ size_t agg_frame_workspace_bytes(const agg_shape* shape);
 int agg_frame_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V, void* O,
                        float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * One global-attention block around the calls above (Sec. 4.2: a converted or subsampled
+ * block keeps all its other components and parameters):
+ *     y = x + W_o * Attn( Q, K, V ) + b_o,   [Q|K|V] = W_{q,k,v} * LayerNorm(x) + b_{q,k,v}
+ * with Attn chosen by `mode`.  x, y: device bf16 [B, N*L, C], C = H*D (y may not alias x).
+ * Weights: device memory; w_*: bf16 [C, C], one row per OUTPUT channel (y = x W^T);
+ * b_* (may be NULL), ln_gamma, ln_beta: float32 [C].  Q, K, V and the attention output
+ * are bf16 tensors in the workspace, as in the calls above.  Rotary embeddings or
+ * query/key normalisation, which the paper's text does not describe, are not applied.
+ */
+typedef struct agg_block_weights {
+  const float* ln_gamma;
+  const float* ln_beta;
+  float ln_eps;
+  const void *w_q, *w_k, *w_v, *w_o;
+  const float *b_q, *b_k, *b_v, *b_o;
+} agg_block_weights;
+
+enum {
+  AGG_BLOCK_SGA = 0,   /* subsampled global attention, Sec. 4.3 (shape's strides and flags) */
+  AGG_BLOCK_FRAME = 1, /* frame attention: the Global-to-Frame conversion, Sec. 4.2         */
+  AGG_BLOCK_DENSE = 2  /* ordinary global attention                                         */
+};
+
+/* Host only.  Scratch bytes agg_global_block_fwd needs for `mode` (0 on an invalid shape). */
+size_t agg_block_workspace_bytes(const agg_shape* shape, int mode);
+
+int agg_global_block_fwd(const agg_shape* shape, int mode, const agg_block_weights* weights,
+                         const void* x, void* y, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

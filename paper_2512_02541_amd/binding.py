@@ -61,7 +61,31 @@ EXPORTS = [
     "agg_dropped_indices_host", "agg_kv_compact_bytes", "agg_kc_offset", "agg_vc_offset", "agg_workspace_bytes",
     "agg_dense_workspace_bytes", "agg_kv_subsample", "agg_global_attn_fwd",
     "agg_dense_global_attn_fwd", "agg_frame_workspace_bytes", "agg_frame_attn_fwd",
+    "agg_block_workspace_bytes", "agg_global_block_fwd",
 ]
+
+AGG_BLOCK_SGA = 0
+AGG_BLOCK_FRAME = 1
+AGG_BLOCK_DENSE = 2
+
+
+class agg_block_weights(ctypes.Structure):
+    _fields_ = [
+        ("ln_gamma", ctypes.c_void_p), ("ln_beta", ctypes.c_void_p), ("ln_eps", ctypes.c_float),
+        ("w_q", ctypes.c_void_p), ("w_k", ctypes.c_void_p), ("w_v", ctypes.c_void_p),
+        ("w_o", ctypes.c_void_p),
+        ("b_q", ctypes.c_void_p), ("b_k", ctypes.c_void_p), ("b_v", ctypes.c_void_p),
+        ("b_o", ctypes.c_void_p),
+    ]
+
+
+def make_block_weights(ln_gamma, ln_beta, ln_eps, w_q, w_k, w_v, w_o, b_q=None, b_k=None,
+                       b_v=None, b_o=None) -> agg_block_weights:
+    """Packs device tensors (kept alive by the caller) into the C struct."""
+    def p(t):
+        return None if t is None else t.data_ptr()
+    return agg_block_weights(p(ln_gamma), p(ln_beta), float(ln_eps), p(w_q), p(w_k), p(w_v),
+                             p(w_o), p(b_q), p(b_k), p(b_v), p(b_o))
 
 
 def lib():
@@ -101,6 +125,10 @@ def lib():
     L.agg_frame_workspace_bytes.restype = ctypes.c_size_t
     L.agg_frame_workspace_bytes.argtypes = [shp]
     L.agg_frame_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.agg_block_workspace_bytes.restype = ctypes.c_size_t
+    L.agg_block_workspace_bytes.argtypes = [shp, ctypes.c_int]
+    L.agg_global_block_fwd.argtypes = [shp, ctypes.c_int, ctypes.POINTER(agg_block_weights), vp, vp,
+                                       vp, ctypes.c_size_t, vp]
     _lib = L
     return L
 
@@ -216,3 +244,13 @@ def agg_frame_attn_fwd(shape, Q, K, V, O, lse, workspace, workspace_bytes, strea
     _check(lib().agg_frame_attn_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
                                     _ptr(lse), _ptr(workspace), int(workspace_bytes),
                                     _stream(stream)), "agg_frame_attn_fwd")
+
+
+def agg_block_workspace_bytes(shape: agg_shape, mode: int) -> int:
+    return int(lib().agg_block_workspace_bytes(ctypes.byref(shape), int(mode)))
+
+
+def agg_global_block_fwd(shape, mode, weights, x, y, workspace, workspace_bytes, stream=None):
+    _check(lib().agg_global_block_fwd(ctypes.byref(shape), int(mode), ctypes.byref(weights),
+                                      _ptr(x), _ptr(y), _ptr(workspace), int(workspace_bytes),
+                                      _stream(stream)), "agg_global_block_fwd")

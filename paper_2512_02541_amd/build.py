@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libagg.so")
-SOURCES = ["agg_api.cpp", "agg_gather.hip", "agg_attn.hip"]
+SOURCES = ["agg_api.cpp", "agg_gather.hip", "agg_attn.hip", "agg_block.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

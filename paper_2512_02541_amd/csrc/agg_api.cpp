@@ -232,4 +232,101 @@ int agg_frame_attn_fwd(const agg_shape* shape, const void* Q, const void* K, con
   return agg_dense_global_attn_fwd(&f, Q, K, V, O, lse, workspace, workspace_bytes, hip_stream);
 }
 
+// ---- one global-attention block --------------------------------------------------------
+namespace {
+
+inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// Workspace layout of agg_global_block_fwd: LayerNorm output, Q, K, V, attention output,
+// then whatever the chosen attention needs.
+struct BlockPlan {
+  size_t act;      // bytes of one [B, N*L, C] bf16 activation
+  size_t attn_ws;  // bytes behind the five activations
+  size_t compact;  // SGA: bytes of one compacted tensor
+  size_t total;
+};
+
+int plan_block(const agg_shape* shape, int mode, BlockPlan* p) {
+  Geom g;
+  int rc = make_geom(shape, &g, mode != AGG_BLOCK_SGA);
+  if (rc != AGG_OK) return rc;
+  if (mode != AGG_BLOCK_SGA && mode != AGG_BLOCK_FRAME && mode != AGG_BLOCK_DENSE)
+    return AGG_ERR_SHAPE;
+  p->act = align256((size_t)g.B * g.NQ * g.H * kHeadDim * 2);
+  p->compact = 0;
+  if (mode == AGG_BLOCK_SGA) {
+    p->compact = align256((size_t)g.B * g.H * g.M_pad * kHeadDim * 2);
+    const size_t means = align256((size_t)g.B * g.H * kHeadDim * sizeof(float));
+    p->attn_ws = 2 * p->compact + 2 * means + align256(agg_workspace_bytes(shape));
+  } else if (mode == AGG_BLOCK_FRAME) {
+    p->attn_ws = align256(agg_frame_workspace_bytes(shape));
+  } else {
+    p->attn_ws = align256(agg_dense_workspace_bytes(shape));
+  }
+  p->total = 5 * p->act + p->attn_ws;
+  return AGG_OK;
+}
+
+}  // namespace
+
+size_t agg_block_workspace_bytes(const agg_shape* shape, int mode) {
+  BlockPlan p;
+  if (plan_block(shape, mode, &p) != AGG_OK) return 0;
+  return p.total;
+}
+
+int agg_global_block_fwd(const agg_shape* shape, int mode, const agg_block_weights* w,
+                         const void* x, void* y, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  BlockPlan p;
+  int rc = plan_block(shape, mode, &p);
+  if (rc != AGG_OK) return rc;
+  if (!w || !x || !y || !workspace || !w->ln_gamma || !w->ln_beta || !w->w_q || !w->w_k ||
+      !w->w_v || !w->w_o)
+    return AGG_ERR_NULL;
+  if (misaligned(x) || misaligned(y) || misaligned(workspace) || misaligned(w->w_q) ||
+      misaligned(w->w_k) || misaligned(w->w_v) || misaligned(w->w_o))
+    return AGG_ERR_ALIGN;
+  if (x == y) return AGG_ERR_SHAPE;
+  if (!(w->ln_eps > 0.0f)) return AGG_ERR_SHAPE;
+  if (workspace_bytes < p.total) return AGG_ERR_WORKSPACE;
+  const int C = shape->H * kHeadDim;
+  if (C > 2048) return AGG_ERR_UNSUPPORTED;  // LayerNorm kernel: one wavefront per row
+  const int64_t rows = (int64_t)shape->B * shape->N * ((int64_t)shape->n_h * shape->n_w + shape->n_special);
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* base = (char*)workspace;
+  void* xn = base;
+  void* Q = base + p.act;
+  void* K = base + 2 * p.act;
+  void* V = base + 3 * p.act;
+  void* A = base + 4 * p.act;  // attention output
+  char* aws = base + 5 * p.act;
+
+  if (launch_layernorm(x, w->ln_gamma, w->ln_beta, xn, rows, C, w->ln_eps, st) != hipSuccess)
+    return AGG_ERR_LAUNCH;
+  if (launch_linear(xn, w->w_q, w->b_q, nullptr, Q, rows, C, C, st) != hipSuccess ||
+      launch_linear(xn, w->w_k, w->b_k, nullptr, K, rows, C, C, st) != hipSuccess ||
+      launch_linear(xn, w->w_v, w->b_v, nullptr, V, rows, C, C, st) != hipSuccess)
+    return AGG_ERR_LAUNCH;
+  if (mode == AGG_BLOCK_SGA) {
+    const size_t means = align256((size_t)shape->B * shape->H * kHeadDim * sizeof(float));
+    void* Kc = aws;
+    void* Vc = aws + p.compact;
+    float* kmean = (float*)(aws + 2 * p.compact);
+    float* vmean = (float*)(aws + 2 * p.compact + means);
+    void* mws = aws + 2 * p.compact + 2 * means;
+    rc = agg_kv_subsample(shape, K, V, Kc, Vc, nullptr, kmean, vmean, mws,
+                          agg_workspace_bytes(shape), hip_stream);
+    if (rc != AGG_OK) return rc;
+    rc = agg_global_attn_fwd(shape, Q, K, V, Kc, Vc, kmean, vmean, A, nullptr, hip_stream);
+  } else if (mode == AGG_BLOCK_FRAME) {
+    rc = agg_frame_attn_fwd(shape, Q, K, V, A, nullptr, aws, p.attn_ws, hip_stream);
+  } else {
+    rc = agg_dense_global_attn_fwd(shape, Q, K, V, A, nullptr, aws, p.attn_ws, hip_stream);
+  }
+  if (rc != AGG_OK) return rc;
+  if (launch_linear(A, w->w_o, w->b_o, x, y, rows, C, C, st) != hipSuccess) return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
 }  // extern "C"

@@ -1,0 +1,243 @@
+// The parts of a global-attention block around the attention itself (AVGGT Sec. 4.2: a
+// block is converted or subsampled with all its other components unchanged):
+// LayerNorm, the Q/K/V projections, the output projection with bias and residual.
+// They are a few percent of a block's time next to attention over 10^5..10^6 tokens, so
+// they are written for clarity on the same MFMA conventions as the attention kernel
+// rather than tuned to the last percent.
+#include "agg_internal.h"
+
+namespace agg {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+namespace {
+
+union Frag {
+  u32x4 u;
+  bf16x8 h;
+};
+
+__device__ inline uint32_t pack2(float lo, float hi) {
+  f32x2 p = {lo, hi};
+  bf16x2 h = __builtin_convertvector(p, bf16x2);
+  return __builtin_bit_cast(uint32_t, h);
+}
+__device__ inline float lo16(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ inline float hi16(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// LayerNorm over the channel dimension: one wavefront per token row, fp32 statistics
+// (mean, then variance of the centred values), bf16 in and out.  C must be a multiple
+// of 8; a lane owns 16-byte chunks lane, lane+64, ...
+// ---------------------------------------------------------------------------
+constexpr int kLnThreads = 256;
+constexpr int kLnMaxChunks = 4;  // per lane: supports C <= 64*8*4 = 2048
+
+__global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* __restrict__ x,
+                                                               const float* __restrict__ gamma,
+                                                               const float* __restrict__ beta,
+                                                               uint16_t* __restrict__ y, int64_t rows,
+                                                               int C, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * (kLnThreads / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nchunk = C / 8;
+  const uint16_t* xr = x + row * C;
+  float v[kLnMaxChunks][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < kLnMaxChunks; ++c) {
+    const int ch = lane + 64 * c;
+    if (ch < nchunk) {
+      u32x4 raw = *reinterpret_cast<const u32x4*>(xr + ch * 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[c][2 * i] = lo16(raw[i]);
+        v[c][2 * i + 1] = hi16(raw[i]);
+        sum += v[c][2 * i] + v[c][2 * i + 1];
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+  const float mean = sum / (float)C;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < kLnMaxChunks; ++c) {
+    const int ch = lane + 64 * c;
+    if (ch < nchunk) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float d = v[c][i] - mean;
+        sq += d * d;
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) sq += __shfl_xor(sq, off);
+  const float rstd = rsqrtf(sq / (float)C + eps);
+  uint16_t* yr = y + row * C;
+#pragma unroll
+  for (int c = 0; c < kLnMaxChunks; ++c) {
+    const int ch = lane + 64 * c;
+    if (ch < nchunk) {
+      float o[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        o[i] = (v[c][i] - mean) * rstd * gamma[ch * 8 + i] + beta[ch * 8 + i];
+      u32x4 w = {pack2(o[0], o[1]), pack2(o[2], o[3]), pack2(o[4], o[5]), pack2(o[6], o[7])};
+      *reinterpret_cast<u32x4*>(yr + ch * 8) = w;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Linear layer  Y[m, n] = sum_k A[m, k] W[n, k] + bias[n] (+ R[m, n]),  bf16 in/out,
+// fp32 accumulation on v_mfma_f32_32x32x16_bf16.  A: [rows, K] row-major; W: [N, K]
+// row-major (one row per output channel), so both operands are contiguous along k.
+// One workgroup computes a 128 x 128 tile with 64-wide k steps, double-buffered in
+// LDS through registers; each of its four wavefronts owns 64 x 64.  LDS rows are 128
+// bytes with the 16-byte chunk index XOR-ed by (row & 7) so that both the row-wise
+// fills and the fragment reads spread over all banks.  The product is formed
+// transposed (W rows as the MFMA A operand) so that a lane ends up with four
+// consecutive output channels of one token: 8-byte stores.
+// Requires K % 64 == 0 and N % 8 == 0.
+// ---------------------------------------------------------------------------
+constexpr int kGemmThreads = 256;
+constexpr int kTM = 128, kTN = 128, kTK = 64;
+
+__device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ (row & 7)); }
+
+__global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, const float* __restrict__ bias,
+    const uint16_t* __restrict__ R, uint16_t* __restrict__ Y, int64_t rows, int N, int K) {
+  __shared__ __align__(16) u32x4 sA[2][kTM * 8];
+  __shared__ __align__(16) u32x4 sW[2][kTN * 8];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int l32 = lane & 31;
+  const int g2 = lane >> 5;
+  const int wm = (wave & 1) * 64;   // this wavefront's 64 token rows inside the tile
+  const int wn = (wave >> 1) * 64;  // and its 64 output channels
+  const int64_t m0 = (int64_t)blockIdx.x * kTM;
+  const int n0 = blockIdx.y * kTN;
+
+  // staging: 128 rows x 8 chunks per operand = 1024 chunks, 4 per thread
+  u32x4 ra[4], rw[4];
+  auto gload = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + i * kGemmThreads;
+      const int r = c >> 3, j = c & 7;
+      int64_t am = m0 + r;
+      if (am >= rows) am = rows - 1;  // tail rows repeat the last row, never stored
+      int wn_ = n0 + r;
+      if (wn_ >= N) wn_ = N - 1;
+      ra[i] = *reinterpret_cast<const u32x4*>(A + am * K + k0 + j * 8);
+      rw[i] = *reinterpret_cast<const u32x4*>(W + (int64_t)wn_ * K + k0 + j * 8);
+    }
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + i * kGemmThreads;
+      const int r = c >> 3, j = c & 7;
+      sA[buf][swz(r, j)] = ra[i];
+      sW[buf][swz(r, j)] = rw[i];
+    }
+  };
+
+  f32x16 acc[2][2];  // [channel block][token block]
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  const int nk = K / kTK;
+  gload(0);
+  lstore(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) gload((kt + 1) * kTK);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      Frag fw[2], fa[2];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        fw[b].u = sW[buf][swz(wn + b * 32 + l32, ks * 2 + g2)];
+        fa[b].u = sA[buf][swz(wm + b * 32 + l32, ks * 2 + g2)];
+      }
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+          acc[a][b] =
+              __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a].h, fa[b].h, acc[a][b], 0, 0, 0);
+    }
+    if (kt + 1 < nk) lstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // acc[a][b][r]: channel n0 + wn + 32a + 8(r/4) + 4g2 + r%4, token m0 + wm + 32b + l32
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int64_t m = m0 + wm + b * 32 + l32;
+    if (m >= rows) continue;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int n = n0 + wn + a * 32 + r4 * 8 + g2 * 4;
+        if (n >= N) continue;
+        float o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = acc[a][b][r4 * 4 + i] + (bias ? bias[n + i] : 0.f);
+        if (R) {
+          u32x2 rr = *reinterpret_cast<const u32x2*>(R + m * N + n);
+          o[0] += lo16(rr[0]);
+          o[1] += hi16(rr[0]);
+          o[2] += lo16(rr[1]);
+          o[3] += hi16(rr[1]);
+        }
+        u32x2 w = {pack2(o[0], o[1]), pack2(o[2], o[3])};
+        *reinterpret_cast<u32x2*>(Y + m * N + n) = w;
+      }
+  }
+}
+
+hipError_t launch_layernorm(const void* x, const float* gamma, const float* beta, void* y,
+                            int64_t rows, int C, float eps, hipStream_t st) {
+  if (C % 8 != 0 || C > 64 * 8 * kLnMaxChunks) return hipErrorInvalidValue;
+  const int64_t groups = (rows + (kLnThreads / 64) - 1) / (kLnThreads / 64);
+  if (groups > 0x7FFFFFFF) return hipErrorInvalidConfiguration;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(layernorm_kernel, dim3((unsigned)groups), dim3(kLnThreads), 0, st,
+                     (const uint16_t*)x, gamma, beta, (uint16_t*)y, rows, C, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_linear(const void* A, const void* W, const float* bias, const void* R, void* Y,
+                         int64_t rows, int N, int K, hipStream_t st) {
+  if (K % kTK != 0 || N % 8 != 0) return hipErrorInvalidValue;
+  const int64_t gm = (rows + kTM - 1) / kTM;
+  const int gn = (N + kTN - 1) / kTN;
+  if (gm > 0x7FFFFFFF || gn > 65535) return hipErrorInvalidConfiguration;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(linear_kernel, dim3((unsigned)gm, (unsigned)gn), dim3(kGemmThreads), 0, st,
+                     (const uint16_t*)A, (const uint16_t*)W, bias, (const uint16_t*)R, (uint16_t*)Y,
+                     rows, N, K);
+  return hipGetLastError();
+}
+
+}  // namespace agg

@@ -122,6 +122,12 @@ hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bi
                        const void* K, const void* V, const void* Kc, const void* Vc,
                        const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st);
 
+hipError_t launch_layernorm(const void* x, const float* gamma, const float* beta, void* y,
+                            int64_t rows, int C, float eps, hipStream_t st);
+// Y[rows, N] = A[rows, K] W[N, K]^T + bias (+ R); bf16 tensors, float bias (may be null)
+hipError_t launch_linear(const void* A, const void* W, const float* bias, const void* R, void* Y,
+                         int64_t rows, int N, int K, hipStream_t st);
+
 int mean_chunks(const Geom& g);  // number of partial-sum blocks the mean kernel uses
 
 }  // namespace agg

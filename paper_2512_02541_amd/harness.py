@@ -101,6 +101,19 @@ def frame_forward(shape, Q, K, V, with_lse=True):
     return O, lse
 
 
+def block_forward(shape, mode, wts, x):
+    """One global-attention block (LayerNorm, projections, attention of `mode`, output
+    projection, residual); wts is the dict of device tensors from inputs.block_weights."""
+    cw = agg.make_block_weights(wts["ln_gamma"], wts["ln_beta"], wts["ln_eps"], wts["w_q"],
+                                wts["w_k"], wts["w_v"], wts["w_o"], wts.get("b_q"), wts.get("b_k"),
+                                wts.get("b_v"), wts.get("b_o"))
+    nws = agg.agg_block_workspace_bytes(shape, mode)
+    ws = torch.empty(nws, dtype=torch.uint8, device=x.device)
+    y = torch.empty_like(x)
+    agg.agg_global_block_fwd(shape, mode, cw, x, y, ws, nws)
+    return y, ws
+
+
 def decode_compact(flat: torch.Tensor, B: int, H: int, M: int, M_pad: int, which: str) -> torch.Tensor:
     """Fragment-order Kc ('k') or Vc ('v') -> plain [B, H, M_pad, 64] (layout of agg.h)."""
     nt = M_pad // 64

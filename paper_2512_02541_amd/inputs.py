@@ -156,3 +156,23 @@ def bf16_bits(t: torch.Tensor):
     import numpy as np
 
     return t.detach().contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def block_weights(C: int, seed: int, device="cpu"):
+    """Random-init parameters of one attention block: LayerNorm scale/shift near (1, 0),
+    projection matrices N(0, 1/C) as bf16 [C_out, C_in], small float32 biases."""
+    s = 1.0 / (C ** 0.5)
+    out = {
+        "ln_gamma": 1.0 + 0.1 * normal_tensor((C,), seed, 20, device),
+        "ln_beta": 0.1 * normal_tensor((C,), seed, 21, device),
+        "ln_eps": 1e-6,
+    }
+    for i, name in enumerate(("q", "k", "v", "o")):
+        out["w_" + name] = (s * normal_tensor((C, C), seed, 30 + i, device)).to(torch.bfloat16)
+        out["b_" + name] = 0.02 * normal_tensor((C,), seed, 40 + i, device)
+    return out
+
+
+def block_input(B: int, NQ: int, C: int, seed: int, device="cpu"):
+    """Block input activations ~ N(0,1), bf16 [B, NQ, C]."""
+    return normal_tensor((B, NQ, C), seed, 50, device).to(torch.bfloat16)

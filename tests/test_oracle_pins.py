@@ -509,3 +509,48 @@ def test_frame_attention_is_block_diagonal_dense_attention():
     Of, _ = orc.frame_rows(one, bits(q), bits(k), bits(v), np.arange(one.NQ))
     Od, _ = orc.dense_rows(one, bits(q), bits(k), bits(v), np.arange(one.NQ))
     assert np.abs(Of - Od).max() == 0.0
+
+
+# ----------------------------------------------------------------------------
+# block oracle: its pieces against library routines, its composition against a
+# second way of writing it
+# ----------------------------------------------------------------------------
+def test_block_oracle_pieces_and_composition():
+    from oracle import block_oracle as blk
+
+    rng = np.random.default_rng(5)
+    # bf16 rounding helper: round-to-nearest-even, ties checked on exact halves
+    vals = np.array([1.0, 1.00390625, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -2.5, 3.0e38, 1e-40])
+    want = torch.tensor(vals, dtype=torch.float64).to(torch.float32).to(torch.bfloat16)
+    got = blk.from_bf16_bits(blk.to_bf16_bits(vals))
+    assert np.array_equal(got, want.to(torch.float64).numpy())
+    # LayerNorm and linear against torch in float64
+    x = rng.standard_normal((3, 7, 128))
+    gamma, beta = rng.standard_normal(128), rng.standard_normal(128)
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(x), (128,), torch.from_numpy(gamma),
+                                         torch.from_numpy(beta), eps=1e-6).numpy()
+    assert np.abs(blk.layernorm(x, gamma, beta, 1e-6) - ref).max() < 1e-12
+    w, b = rng.standard_normal((64, 128)), rng.standard_normal(64)
+    ref = torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(w), torch.from_numpy(b))
+    assert np.abs(blk.linear(x, w, b) - ref.numpy()).max() < 1e-12
+    # composition: with identity projections, unit LayerNorm scale and zero biases the block is
+    # x + Attn(LN(x), LN(x), LN(x)) on the bf16-rounded LayerNorm output
+    shape = small_shape(B=1, N=2, n_h=3, n_w=4, H=2, D=8, flags=orc.DIAG | orc.MEAN)
+    C = shape.H * shape.D
+    xb = blk.to_bf16_bits(rng.standard_normal((1, shape.NQ, C)))
+    eye = np.eye(C)
+    wts = dict(ln_gamma=np.ones(C), ln_beta=np.zeros(C), ln_eps=1e-6, w_q=eye, w_k=eye, w_v=eye,
+               w_o=eye)
+    for mode in (blk.SGA, blk.FRAME, blk.DENSE):
+        y = blk.block(shape, mode, xb, wts)
+        x = blk.from_bf16_bits(xb)
+        xn = blk.to_bf16_bits(blk.layernorm(x, 1.0, 0.0, 1e-6)).reshape(1, shape.NQ, shape.H, shape.D)
+        rows = np.arange(shape.NQ)
+        if mode == blk.SGA:
+            o = orc.sga(shape, xn, xn, xn)["O"]
+        elif mode == blk.FRAME:
+            o, _ = orc.frame_rows(shape, xn, xn, xn, rows)
+        else:
+            o, _ = orc.dense_rows(shape, xn, xn, xn, rows)
+        o = blk.from_bf16_bits(blk.to_bf16_bits(o)).reshape(1, shape.NQ, C)
+        assert np.array_equal(y, blk.from_bf16_bits(blk.to_bf16_bits(x + o)))
