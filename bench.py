@@ -244,6 +244,88 @@ def run_sweep(args, log):
     return 0
 
 
+def run_block(args, log):
+    """The global-attention blocks of one aggregator pass at full width (dim 1024 = 16 x 64):
+    LayerNorm, Q/K/V projections, attention, output projection and residual per block;
+    `--layers` blocks chained, the first `--t-early` of them as per-frame attention
+    (Global-to-Frame conversion, Sec. 4.2), the rest subsampled (Sec. 4.3).  One dense
+    block is timed beside them for the ratio.  Random-init weights, one set per layer."""
+    import torch
+
+    from paper_2512_02541_amd import binding as agg
+    from paper_2512_02541_amd import harness, inputs
+
+    w = inputs.WORKLOADS[args.workload]
+    shape = harness.shape_of(w)
+    C = w.H * w.D
+    log("block stack on %s: %d tokens x %d channels, %d layers (%d as frame attention)" % (
+        args.workload, w.NQ, C, args.layers, args.t_early))
+    x0 = inputs.block_input(w.B, w.NQ, C, w.seed, "cuda")
+    layers = [inputs.block_weights(C, w.seed + 1 + i, "cuda") for i in range(args.layers)]
+    cws = [agg.make_block_weights(l["ln_gamma"], l["ln_beta"], l["ln_eps"], l["w_q"], l["w_k"],
+                                  l["w_v"], l["w_o"], l["b_q"], l["b_k"], l["b_v"], l["b_o"])
+           for l in layers]
+    modes = [agg.AGG_BLOCK_FRAME if i < args.t_early else agg.AGG_BLOCK_SGA
+             for i in range(args.layers)]
+    nws = max(agg.agg_block_workspace_bytes(shape, m) for m in
+              (agg.AGG_BLOCK_FRAME, agg.AGG_BLOCK_SGA, agg.AGG_BLOCK_DENSE))
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    xa, xb = torch.empty_like(x0), torch.empty_like(x0)
+
+    def stack():
+        src = x0
+        for i in range(args.layers):
+            dst = xa if (i % 2 == 0) else xb
+            agg.agg_global_block_fwd(shape, modes[i], cws[i], src, dst, ws, nws)
+            src = dst
+        return src
+
+    for _ in range(args.warmup):
+        stack()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = stack()
+    torch.cuda.synchronize()
+    ms_stack = (time.perf_counter() - t0) * 1e3 / args.steps
+    finite = bool(torch.isfinite(out[:, ::997].float()).all().item())
+
+    def one(mode, n):
+        return time_events(lambda: agg.agg_global_block_fwd(shape, mode, cws[-1], x0, xa, ws, nws),
+                           n, 1)[0]
+
+    ms_sga = one(agg.AGG_BLOCK_SGA, args.steps)
+    ms_frame = one(agg.AGG_BLOCK_FRAME, args.steps)
+    ms_dense = one(agg.AGG_BLOCK_DENSE, 1) if not args.no_dense else None
+    M, _ = agg.agg_kv_count(shape)
+    proj_flops = 4 * 2.0 * w.NQ * C * C
+    fl_sga = sga_flops(w.NQ, M, w.H, w.D) + proj_flops
+    fl_frame = 4.0 * w.N * w.L * w.L * w.D * w.H + proj_flops
+    fl_stack = args.t_early * fl_frame + (args.layers - args.t_early) * fl_sga
+    res = {
+        "metric": "ms per aggregator pass over the global-attention blocks (LayerNorm + QKV "
+                  "projection + attention + output projection + residual)",
+        "value": ms_stack, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_stack, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s block stack: %d frames x (37x37+5) tokens, dim %d, %d global "
+                               "blocks, first %d as frame attention, rest subsampled with strides "
+                               "(%d,%d), diag+mean" % (args.workload, w.N, C, args.layers,
+                                                       args.t_early, w.s_h, w.s_w),
+                   "NQ": w.NQ, "M": M, "ms_block_sga": ms_sga, "ms_block_frame": ms_frame,
+                   "ms_block_dense": ms_dense,
+                   "tflops_block_sga": fl_sga / (ms_sga * 1e-3) / 1e12,
+                   "tflops_block_frame": fl_frame / (ms_frame * 1e-3) / 1e12,
+                   "tflops_stack": fl_stack / (ms_stack * 1e-3) / 1e12,
+                   "projection_flops_per_block": proj_flops,
+                   "ms_stack_if_all_dense": (ms_dense * args.layers) if ms_dense else None,
+                   "speedup_vs_all_dense": (ms_dense * args.layers / ms_stack) if ms_dense else None,
+                   "output_finite": finite},
+    }
+    print(json.dumps(res), flush=True)
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -258,6 +340,12 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="time the method's variants on --workload (sigma 2/4/6/9, both first-frame "
                          "rules, the four diag/mean flag combinations) and print one JSON line")
+    ap.add_argument("--block", action="store_true",
+                    help="time the chained global-attention blocks (LayerNorm, projections, "
+                         "attention, residual) on --workload instead of the bare attention path")
+    ap.add_argument("--layers", type=int, default=12)
+    ap.add_argument("--t-early", type=int, default=4,
+                    help="with --block: leading blocks run as per-frame attention")
     ap.add_argument("--only", choices=["attn", "gather", "dense", "copy"], default=None,
                     help="profiling aid: launch just this piece `steps` times (for rocprofv3 runs)")
     args = ap.parse_args()
@@ -282,6 +370,8 @@ def main():
         return run_only(args, log)
     if args.sweep:
         return run_sweep(args, log)
+    if args.block:
+        return run_block(args, log)
 
     res, ctx = run_workload(args.workload, args.steps, args.warmup, not args.no_dense, log)
     cpu, parity = (None, None)
