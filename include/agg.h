@@ -184,6 +184,61 @@ int agg_global_block_fwd(const agg_shape* shape, int mode, const agg_block_weigh
                          const void* x, void* y, void* workspace, size_t workspace_bytes,
                          void* hip_stream);
 
+/*
+ * ---- Caller-supplied key/value sets (supplementary ablation on the grid strategy) ----
+ * The paper compares its fixed choice (first token of each window) with other choices of one
+ * token per window: a random one, the one with the highest and the one with the lowest feature
+ * magnitude.  These calls run the same attention over ANY list of kept tokens:
+ *   list       device int32 [B, M_list]: token ids (0 <= id < N*L) whose K/V rows serve as
+ *              keys/values of that batch element, in any order.  Ids outside the range are
+ *              clamped into it (memory-safe, meaningless result); a repeated id counts twice.
+ *   kept_bits  device uint32 [B, ceil(N*L/32)]: bit t%32 of word t/32 set <=> token t is listed
+ *   n_dropped  device int32 [B]: patch tokens (slot >= n_special) that are not listed
+ * The self term (AGG_DIAG) applies to every query whose token is not listed, the mean
+ * component (AGG_MEAN) averages K resp. V over the unlisted patch tokens and is present when
+ * n_dropped[b] > 0.  shape->s_h, s_w, keep_first_frame matter only to agg_select_kv_indices.
+ */
+enum {
+  AGG_SELECT_FIRST = 0,  /* top-left token of each window: the paper's rule (Sec. 4.3)        */
+  AGG_SELECT_RANDOM = 1, /* a pseudo-random token of each window                              */
+  AGG_SELECT_HIGH = 2,   /* the token of each window with the largest sum of squares of its K */
+  AGG_SELECT_LOW = 3     /* ... with the smallest                                             */
+};
+
+/*
+ * Writes list[B, M] (M of agg_kv_count): row m of batch b is the token chosen for the m-th
+ * kept position of the grid rule -- special tokens and (keep_first_frame) frame 0 map to
+ * themselves, the m-th window of a subsampled frame to one of its tokens by `rule`:
+ *   RANDOM: cell number  mix(mix(s ^ (b*N+frame)*0x85EBCA77) ^ window*0xC2B2AE3D) % cells,
+ *           s = (uint32)seed ^ (uint32)(seed>>32)*0x9E3779B1, window = row-major window number
+ *           inside the frame, cells counted row-major inside the (possibly clipped) window,
+ *           mix(x): x^=x>>16; x*=0x7FEB352D; x^=x>>15; x*=0x846CA68B; x^=x>>16  (32-bit);
+ *   HIGH/LOW: magnitude = sum over all H*D channels of K[b, token]^2 in float32; ties go to
+ *           the earlier cell.
+ * K: device bf16 [B, N*L, H, D]; read only for HIGH/LOW (may be NULL otherwise).
+ */
+int agg_select_kv_indices(const agg_shape* shape, int rule, uint64_t seed, const void* K,
+                          int32_t* list, void* hip_stream);
+
+/* Host only.  Size of ONE compacted tensor for a list of M_list rows, and its M_pad. */
+int agg_list_compact_bytes(const agg_shape* shape, int64_t M_list, size_t* bytes, int64_t* M_pad);
+
+/* Host only.  Scratch bytes agg_kv_subsample_list needs (0 on an invalid shape). */
+size_t agg_list_workspace_bytes(const agg_shape* shape);
+
+/* As agg_kv_subsample, for a caller's list: Kc/Vc (agg_list_compact_bytes each; row m of batch
+ * b = token list[b, m]), kmean/vmean [B,H,D], kept_bits and n_dropped as defined above. */
+int agg_kv_subsample_list(const agg_shape* shape, const int32_t* list, int64_t M_list,
+                          const void* K, const void* V, void* Kc, void* Vc, float* kmean,
+                          float* vmean, uint32_t* kept_bits, int32_t* n_dropped, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
+/* As agg_global_attn_fwd, over what agg_kv_subsample_list wrote for the same shape and M_list. */
+int agg_global_attn_fwd_list(const agg_shape* shape, int64_t M_list, const void* Q, const void* K,
+                             const void* V, const void* Kc, const void* Vc, const float* kmean,
+                             const float* vmean, const uint32_t* kept_bits,
+                             const int32_t* n_dropped, void* O, float* lse, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -62,7 +62,14 @@ EXPORTS = [
     "agg_dense_workspace_bytes", "agg_kv_subsample", "agg_global_attn_fwd",
     "agg_dense_global_attn_fwd", "agg_frame_workspace_bytes", "agg_frame_attn_fwd",
     "agg_block_workspace_bytes", "agg_global_block_fwd",
+    "agg_select_kv_indices", "agg_list_compact_bytes", "agg_list_workspace_bytes",
+    "agg_kv_subsample_list", "agg_global_attn_fwd_list",
 ]
+
+AGG_SELECT_FIRST = 0
+AGG_SELECT_RANDOM = 1
+AGG_SELECT_HIGH = 2
+AGG_SELECT_LOW = 3
 
 AGG_BLOCK_SGA = 0
 AGG_BLOCK_FRAME = 1
@@ -129,6 +136,14 @@ def lib():
     L.agg_block_workspace_bytes.argtypes = [shp, ctypes.c_int]
     L.agg_global_block_fwd.argtypes = [shp, ctypes.c_int, ctypes.POINTER(agg_block_weights), vp, vp,
                                        vp, ctypes.c_size_t, vp]
+    L.agg_select_kv_indices.argtypes = [shp, ctypes.c_int, ctypes.c_uint64, vp, vp, vp]
+    L.agg_list_compact_bytes.argtypes = [shp, ctypes.c_int64, ctypes.POINTER(ctypes.c_size_t), i64p]
+    L.agg_list_workspace_bytes.restype = ctypes.c_size_t
+    L.agg_list_workspace_bytes.argtypes = [shp]
+    L.agg_kv_subsample_list.argtypes = [shp, vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                        ctypes.c_size_t, vp]
+    L.agg_global_attn_fwd_list.argtypes = [shp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                           vp, vp, vp]
     _lib = L
     return L
 
@@ -254,3 +269,36 @@ def agg_global_block_fwd(shape, mode, weights, x, y, workspace, workspace_bytes,
     _check(lib().agg_global_block_fwd(ctypes.byref(shape), int(mode), ctypes.byref(weights),
                                       _ptr(x), _ptr(y), _ptr(workspace), int(workspace_bytes),
                                       _stream(stream)), "agg_global_block_fwd")
+
+
+def agg_select_kv_indices(shape, rule, seed, K, list_out, stream=None):
+    _check(lib().agg_select_kv_indices(ctypes.byref(shape), int(rule), int(seed), _ptr(K),
+                                       _ptr(list_out), _stream(stream)), "agg_select_kv_indices")
+
+
+def agg_list_compact_bytes(shape: agg_shape, M_list: int):
+    nbytes, m_pad = ctypes.c_size_t(0), ctypes.c_int64(0)
+    _check(lib().agg_list_compact_bytes(ctypes.byref(shape), int(M_list), ctypes.byref(nbytes),
+                                        ctypes.byref(m_pad)), "agg_list_compact_bytes")
+    return nbytes.value, m_pad.value
+
+
+def agg_list_workspace_bytes(shape: agg_shape) -> int:
+    return int(lib().agg_list_workspace_bytes(ctypes.byref(shape)))
+
+
+def agg_kv_subsample_list(shape, list_in, M_list, K, V, Kc, Vc, kmean, vmean, kept_bits, n_dropped,
+                          workspace, workspace_bytes, stream=None):
+    _check(lib().agg_kv_subsample_list(ctypes.byref(shape), _ptr(list_in), int(M_list), _ptr(K),
+                                       _ptr(V), _ptr(Kc), _ptr(Vc), _ptr(kmean), _ptr(vmean),
+                                       _ptr(kept_bits), _ptr(n_dropped), _ptr(workspace),
+                                       int(workspace_bytes), _stream(stream)),
+           "agg_kv_subsample_list")
+
+
+def agg_global_attn_fwd_list(shape, M_list, Q, K, V, Kc, Vc, kmean, vmean, kept_bits, n_dropped, O,
+                             lse=None, stream=None):
+    _check(lib().agg_global_attn_fwd_list(ctypes.byref(shape), int(M_list), _ptr(Q), _ptr(K),
+                                          _ptr(V), _ptr(Kc), _ptr(Vc), _ptr(kmean), _ptr(vmean),
+                                          _ptr(kept_bits), _ptr(n_dropped), _ptr(O), _ptr(lse),
+                                          _stream(stream)), "agg_global_attn_fwd_list")

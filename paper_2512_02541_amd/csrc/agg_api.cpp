@@ -232,6 +232,88 @@ int agg_frame_attn_fwd(const agg_shape* shape, const void* Q, const void* K, con
   return agg_dense_global_attn_fwd(&f, Q, K, V, O, lse, workspace, workspace_bytes, hip_stream);
 }
 
+// ---- caller-supplied kept lists ---------------------------------------------------------
+// Geometry of the list variants: the grid fields stay (the select kernel needs them), the
+// compacted length becomes the list's.
+static int list_geom(const agg_shape* shape, int64_t M_list, Geom* g) {
+  int rc = make_geom(shape, g, false);
+  if (rc != AGG_OK) return rc;
+  if (M_list < 1) return AGG_ERR_SHAPE;
+  if (M_list > (int64_t)INT32_MAX - 2 * kTileRows) return AGG_ERR_OVERFLOW;
+  g->M = M_list;
+  g->M_pad = ceil_div(M_list, kTileRows) * kTileRows;
+  if ((int64_t)g->B * g->H > ((int64_t)1 << 40) / g->M_pad) return AGG_ERR_OVERFLOW;
+  return AGG_OK;
+}
+
+int agg_select_kv_indices(const agg_shape* shape, int rule, uint64_t seed, const void* K,
+                          int32_t* list, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (rule < AGG_SELECT_FIRST || rule > AGG_SELECT_LOW) return AGG_ERR_SHAPE;
+  const bool needs_k = (rule == AGG_SELECT_HIGH || rule == AGG_SELECT_LOW);
+  if (!list || (needs_k && !K)) return AGG_ERR_NULL;
+  if ((needs_k && misaligned(K)) || ((uintptr_t)list & 3u)) return AGG_ERR_ALIGN;
+  if (launch_select(g, rule, seed, K, list, (hipStream_t)hip_stream) != hipSuccess)
+    return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
+int agg_list_compact_bytes(const agg_shape* shape, int64_t M_list, size_t* bytes, int64_t* M_pad) {
+  Geom g;
+  int rc = list_geom(shape, M_list, &g);
+  if (rc != AGG_OK) return rc;
+  if (bytes) *bytes = (size_t)g.B * g.H * g.M_pad * kHeadDim * 2;
+  if (M_pad) *M_pad = g.M_pad;
+  return AGG_OK;
+}
+
+size_t agg_list_workspace_bytes(const agg_shape* shape) {
+  Geom g;
+  if (make_geom(shape, &g, false) != AGG_OK) return 0;
+  return list_workspace_bytes(g);
+}
+
+int agg_kv_subsample_list(const agg_shape* shape, const int32_t* list, int64_t M_list,
+                          const void* K, const void* V, void* Kc, void* Vc, float* kmean,
+                          float* vmean, uint32_t* kept_bits, int32_t* n_dropped, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  Geom g;
+  int rc = list_geom(shape, M_list, &g);
+  if (rc != AGG_OK) return rc;
+  if (!list || !K || !V || !Kc || !Vc || !kmean || !vmean || !kept_bits || !n_dropped || !workspace)
+    return AGG_ERR_NULL;
+  if (misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) || misaligned(workspace) ||
+      ((uintptr_t)kmean & 3u) || ((uintptr_t)vmean & 3u) || ((uintptr_t)list & 3u) ||
+      ((uintptr_t)kept_bits & 3u) || ((uintptr_t)n_dropped & 3u))
+    return AGG_ERR_ALIGN;
+  if (workspace_bytes < list_workspace_bytes(g)) return AGG_ERR_WORKSPACE;
+  if (launch_subsample_list(g, list, K, V, Kc, Vc, kmean, vmean, kept_bits, n_dropped, workspace,
+                            (hipStream_t)hip_stream) != hipSuccess)
+    return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
+int agg_global_attn_fwd_list(const agg_shape* shape, int64_t M_list, const void* Q, const void* K,
+                             const void* V, const void* Kc, const void* Vc, const float* kmean,
+                             const float* vmean, const uint32_t* kept_bits,
+                             const int32_t* n_dropped, void* O, float* lse, void* hip_stream) {
+  Geom g;
+  int rc = list_geom(shape, M_list, &g);
+  if (rc != AGG_OK) return rc;
+  if (!Q || !K || !V || !Kc || !Vc || !kmean || !vmean || !kept_bits || !n_dropped || !O)
+    return AGG_ERR_NULL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) ||
+      misaligned(O) || ((uintptr_t)kmean & 15u) || ((uintptr_t)vmean & 15u) ||
+      ((uintptr_t)lse & 3u) || ((uintptr_t)kept_bits & 3u) || ((uintptr_t)n_dropped & 3u))
+    return AGG_ERR_ALIGN;
+  if (launch_attn(g, shape->flags, shape->scale, shape->mean_logit_bias, Q, K, V, Kc, Vc, kmean,
+                  vmean, O, lse, (hipStream_t)hip_stream, kept_bits, n_dropped) != hipSuccess)
+    return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
 // ---- one global-attention block --------------------------------------------------------
 namespace {
 

@@ -152,7 +152,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
     const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const uint16_t* __restrict__ Kc, const uint16_t* __restrict__ Vc,
     const float* __restrict__ kmean, const float* __restrict__ vmean, uint16_t* __restrict__ O,
-    float* __restrict__ lse, int nqt, int npairs) {
+    float* __restrict__ lse, int nqt, int npairs, const uint32_t* __restrict__ kept_bits,
+    const int32_t* __restrict__ nd_dev) {
   __shared__ __align__(16) uint16_t sK[kLdsTiles][kTileElems];
   __shared__ __align__(16) uint16_t sV[kLdsTiles][kTileElems];
 
@@ -184,8 +185,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
   Frag Qf[2][4];
   bool dropped[2];
   float l_self[2], l_mean[2];  // base-2 logits of the extras (-inf when absent)
-  const bool use_mean = (flags & AGG_MEAN) && g.n_dropped > 0;
-  const bool use_diag = (flags & AGG_DIAG) && g.n_dropped > 0;
+  // caller's list: membership comes from a bitmap, the dropped count from device memory
+  const int64_t n_drop = nd_dev ? (int64_t)nd_dev[b] : g.n_dropped;
+  const bool use_mean = (flags & AGG_MEAN) && n_drop > 0;
+  const bool use_diag = (flags & AGG_DIAG) && (kept_bits != nullptr || n_drop > 0);
+  const uint32_t* kb = kept_bits ? kept_bits + (int64_t)b * ((g.NQ + 31) / 32) : nullptr;
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb) {
     const int64_t q = (int64_t)qt * kQTile + wave * 64 + qb * 32 + l32;
@@ -199,7 +203,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
         Qf[qb][ks].u[i] = pack_bf16(bf16_lo(raw[i]) * qscale, bf16_hi(raw[i]) * qscale);
     }
     // logits of the extras: lanes l and l^32 hold the two halves of the channel range
-    dropped[qb] = use_diag && q < g.NQ && token_is_dropped(g, q);
+    dropped[qb] = use_diag && q < g.NQ &&
+                  (kb ? ((kb[q >> 5] >> (q & 31)) & 1u) == 0u : (bool)token_is_dropped(g, q));
     float dot_self = 0.f, dot_mean = 0.f;
     if (use_mean || use_diag) {
       const float* km = kmean + ((int64_t)b * g.H + h) * kHeadDim;
@@ -475,7 +480,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
 
 hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bias, const void* Q,
                        const void* K, const void* V, const void* Kc, const void* Vc,
-                       const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st) {
+                       const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st,
+                       const uint32_t* kept_bits, const int32_t* nd_dev) {
   const int nqt = (int)((g.NQ + kQTile - 1) / kQTile);
   const int npairs = g.B * g.H;
   const int64_t groups = (int64_t)((npairs + kXcds - 1) / kXcds) * kXcds * nqt;
@@ -484,7 +490,7 @@ hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bi
   hipLaunchKernelGGL(sga_attn_kernel, dim3((unsigned)groups), dim3(kAttnThreads), 0, st, g, flags,
                      scale * kLog2e, mean_bias * kLog2e, (const uint16_t*)Q, (const uint16_t*)K,
                      (const uint16_t*)V, (const uint16_t*)Kc, (const uint16_t*)Vc, kmean, vmean,
-                     (uint16_t*)O, lse, nqt, npairs);
+                     (uint16_t*)O, lse, nqt, npairs, kept_bits, nd_dev);
   return hipGetLastError();
 }
 

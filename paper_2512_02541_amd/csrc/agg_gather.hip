@@ -31,7 +31,8 @@ struct GatherLds {
 __device__ inline void gather_tile(const Geom& g, const uint16_t* __restrict__ K,
                                    const uint16_t* __restrict__ V, uint16_t* __restrict__ Kc,
                                    uint16_t* __restrict__ Vc, int32_t* __restrict__ idx,
-                                   int64_t tile, int hgrp, int b, GatherLds& s) {
+                                   const int32_t* __restrict__ list, int64_t tile, int hgrp, int b,
+                                   GatherLds& s) {
   const int tid = threadIdx.x;
   const int h0 = hgrp * kHeadGroup;
   const int64_t m0 = tile * kTileRows;
@@ -39,7 +40,15 @@ __device__ inline void gather_tile(const Geom& g, const uint16_t* __restrict__ K
 
   if (tid < kTileRows) {
     int64_t m = m0 + tid;
-    int64_t tok = (m < g.M) ? kept_row_to_token(g, m) : -1;
+    int64_t tok = -1;
+    if (m < g.M) {
+      if (list) {  // caller's list: clamp so that a bad id cannot leave the tensor
+        int64_t t = list[(int64_t)b * g.M + m];
+        tok = t < 0 ? 0 : (t >= g.NQ ? g.NQ - 1 : t);
+      } else {
+        tok = kept_row_to_token(g, m);
+      }
+    }
     s.tok[tid] = tok;
     if (idx && b == 0 && hgrp == 0 && m < g.M) idx[m] = (int32_t)tok;
   }
@@ -103,6 +112,7 @@ constexpr int kMeanMaxChunks = 4096;  // upper bound on partials per batch eleme
 struct MeanLds {
   float red[kSubThreads][17];
   int32_t tok[kMeanBatch];
+  int32_t wcnt[kSubThreads / 64];
 };
 
 // Geometry of the mean role, derived on the host
@@ -137,60 +147,42 @@ __device__ inline void add_bf16x8(float (&acc)[8], const u32x4& v) {
   }
 }
 
-// Mean role.  Threads are laid out as (row lane, 16-byte chunk of the row).  Token ids of the
-// run are resolved kMeanBatch at a time into LDS (one integer division chain per row instead
-// of one per load), and four rows per lane are requested before any is added, so that enough
-// bytes are in flight to cover HBM latency.
-__device__ inline void mean_partial(const Geom& g, const uint16_t* __restrict__ K,
-                                    const uint16_t* __restrict__ V, float* __restrict__ partial,
-                                    const MeanPlan& p, int chunk, int colblk, int b, MeanLds& s) {
-  const int tid = threadIdx.x;
-  const int C = g.H * kHeadDim;
-  const int cg = tid % p.cpr_b;                        // 16-byte chunk inside this channel block
-  const int rl = tid / p.cpr_b;                        // row lane
-  const int col = (colblk * kSubThreads + cg) * 8;     // first channel of this thread
-  const int rpp = p.rpp;
-  const bool active = (rl < rpp) && (col < C);
-  const uint16_t* Kb = K + (int64_t)b * g.NQ * C + col;
-  const uint16_t* Vb = V + (int64_t)b * g.NQ * C + col;
-
-  float ak[8], av[8];
+// Adds the rows s.tok[0..n) (token ids) of K and V into the thread's accumulators.  Threads
+// are laid out as (row lane rl, 16-byte chunk of the row); four rows per lane are requested
+// before any is added, so that enough bytes are in flight to cover HBM latency.
+__device__ inline void add_rows(const MeanLds& s, int n, int rl, int rpp, int C,
+                                const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
+                                float (&ak)[8], float (&av)[8]) {
+  int r = rl;
+  for (; r + 3 * rpp < n; r += 4 * rpp) {
+    u32x4 kv[4], vv[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) ak[i] = av[i] = 0.f;
-
-  const int64_t u0 = (int64_t)chunk * p.rows_per_chunk;
-  const int64_t u1 = min(u0 + p.rows_per_chunk, g.n_dropped);
-  for (int64_t base = u0; base < u1; base += kMeanBatch) {
-    const int n = (int)min((int64_t)kMeanBatch, u1 - base);
-    __syncthreads();  // previous batch consumed
-    if (tid < n) s.tok[tid] = (int32_t)dropped_to_token(g, base + tid);
-    __syncthreads();
-    if (active) {
-      int r = rl;
-      for (; r + 3 * rpp < n; r += 4 * rpp) {
-        u32x4 kv[4], vv[4];
+    for (int j = 0; j < 4; ++j) {
+      const int64_t off = (int64_t)s.tok[r + j * rpp] * C;
+      kv[j] = *reinterpret_cast<const u32x4*>(Kb + off);
+      vv[j] = *reinterpret_cast<const u32x4*>(Vb + off);
+    }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int64_t off = (int64_t)s.tok[r + j * rpp] * C;
-          kv[j] = *reinterpret_cast<const u32x4*>(Kb + off);
-          vv[j] = *reinterpret_cast<const u32x4*>(Vb + off);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          add_bf16x8(ak, kv[j]);
-          add_bf16x8(av, vv[j]);
-        }
-      }
-      for (; r < n; r += rpp) {
-        const int64_t off = (int64_t)s.tok[r] * C;
-        u32x4 kv = *reinterpret_cast<const u32x4*>(Kb + off);
-        u32x4 vv = *reinterpret_cast<const u32x4*>(Vb + off);
-        add_bf16x8(ak, kv);
-        add_bf16x8(av, vv);
-      }
+    for (int j = 0; j < 4; ++j) {
+      add_bf16x8(ak, kv[j]);
+      add_bf16x8(av, vv[j]);
     }
   }
-  // combine the row lanes in ascending order (fixed order -> reproducible)
+  for (; r < n; r += rpp) {
+    const int64_t off = (int64_t)s.tok[r] * C;
+    u32x4 kv = *reinterpret_cast<const u32x4*>(Kb + off);
+    u32x4 vv = *reinterpret_cast<const u32x4*>(Vb + off);
+    add_bf16x8(ak, kv);
+    add_bf16x8(av, vv);
+  }
+}
+
+// Combines the row lanes in ascending order (fixed order -> reproducible) and writes the
+// workgroup's partial sums.
+__device__ inline void write_partial(MeanLds& s, const float (&ak)[8], const float (&av)[8],
+                                     float* __restrict__ partial, const MeanPlan& p, int chunk,
+                                     int b, int rl, int cg, int col, int C) {
+  const int tid = threadIdx.x;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     s.red[tid][i] = ak[i];
@@ -201,7 +193,7 @@ __device__ inline void mean_partial(const Geom& g, const uint16_t* __restrict__ 
     float sk[8], sv[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) sk[i] = sv[i] = 0.f;
-    for (int r = 0; r < rpp; ++r) {
+    for (int r = 0; r < p.rpp; ++r) {
       int t = r * p.cpr_b + cg;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -217,6 +209,90 @@ __device__ inline void mean_partial(const Geom& g, const uint16_t* __restrict__ 
       pv[i] = sv[i];
     }
   }
+}
+
+// Mean role of the grid rule: the run's dropped rows are numbered arithmetically; their token
+// ids are resolved kMeanBatch at a time into LDS (one integer division chain per row instead
+// of one per load).
+__device__ inline void mean_partial(const Geom& g, const uint16_t* __restrict__ K,
+                                    const uint16_t* __restrict__ V, float* __restrict__ partial,
+                                    const MeanPlan& p, int chunk, int colblk, int b, MeanLds& s) {
+  const int tid = threadIdx.x;
+  const int C = g.H * kHeadDim;
+  const int cg = tid % p.cpr_b;                        // 16-byte chunk inside this channel block
+  const int rl = tid / p.cpr_b;                        // row lane
+  const int col = (colblk * kSubThreads + cg) * 8;     // first channel of this thread
+  const bool active = (rl < p.rpp) && (col < C);
+  const uint16_t* Kb = K + (int64_t)b * g.NQ * C + col;
+  const uint16_t* Vb = V + (int64_t)b * g.NQ * C + col;
+
+  float ak[8], av[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ak[i] = av[i] = 0.f;
+
+  const int64_t u0 = (int64_t)chunk * p.rows_per_chunk;
+  const int64_t u1 = min(u0 + p.rows_per_chunk, g.n_dropped);
+  for (int64_t base = u0; base < u1; base += kMeanBatch) {
+    const int n = (int)min((int64_t)kMeanBatch, u1 - base);
+    __syncthreads();  // previous batch consumed
+    if (tid < n) s.tok[tid] = (int32_t)dropped_to_token(g, base + tid);
+    __syncthreads();
+    if (active) add_rows(s, n, rl, p.rpp, C, Kb, Vb, ak, av);
+  }
+  write_partial(s, ak, av, partial, p, chunk, b, rl, cg, col, C);
+}
+
+// Mean role for a caller's list: the run is a range of token ids; a token is summed when it is
+// a patch (slot >= P) whose bit in kept_bits is clear.  Each pass tests kMeanBatch candidates
+// and packs the survivors' ids into LDS in ascending order (ballot + prefix count).
+__device__ inline void mean_partial_bits(const Geom& g, const uint16_t* __restrict__ K,
+                                         const uint16_t* __restrict__ V,
+                                         const uint32_t* __restrict__ bits, int64_t nwords,
+                                         float* __restrict__ partial, int32_t* __restrict__ cnt,
+                                         const MeanPlan& p, int chunk, int colblk, int b,
+                                         MeanLds& s) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int C = g.H * kHeadDim;
+  const int cg = tid % p.cpr_b;
+  const int rl = tid / p.cpr_b;
+  const int col = (colblk * kSubThreads + cg) * 8;
+  const bool active = (rl < p.rpp) && (col < C);
+  const uint16_t* Kb = K + (int64_t)b * g.NQ * C + col;
+  const uint16_t* Vb = V + (int64_t)b * g.NQ * C + col;
+  const uint32_t* bb = bits + (int64_t)b * nwords;
+
+  float ak[8], av[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ak[i] = av[i] = 0.f;
+
+  const int64_t t0 = (int64_t)chunk * p.rows_per_chunk;
+  const int64_t t1 = min(t0 + p.rows_per_chunk, g.NQ);
+  int total = 0;
+  for (int64_t base = t0; base < t1; base += kMeanBatch) {
+    __syncthreads();  // previous batch consumed
+    const int64_t t = base + tid;
+    bool d = false;
+    if (t < t1) {
+      const uint32_t slot = (uint32_t)t % (uint32_t)g.L;
+      if ((int32_t)slot >= g.P) d = ((bb[t >> 5] >> (t & 31)) & 1u) == 0u;
+    }
+    const unsigned long long mask = __ballot(d);
+    if (lane == 0) s.wcnt[wave] = __popcll(mask);
+    __syncthreads();
+    int off = 0, n = 0;
+#pragma unroll
+    for (int w = 0; w < kSubThreads / 64; ++w) {
+      if (w < wave) off += s.wcnt[w];
+      n += s.wcnt[w];
+    }
+    if (d) s.tok[off + __popcll(mask & ((1ull << lane) - 1ull))] = (int32_t)t;
+    __syncthreads();
+    total += n;
+    if (active) add_rows(s, n, rl, p.rpp, C, Kb, Vb, ak, av);
+  }
+  if (tid == 0 && colblk == 0) cnt[(int64_t)b * p.nchunks + chunk] = total;
+  write_partial(s, ak, av, partial, p, chunk, b, rl, cg, col, C);
 }
 
 union SubLds {
@@ -238,7 +314,7 @@ __global__ __launch_bounds__(kSubThreads) void subsample_kernel(
     mean_partial(g, K, V, partial, plan, r / plan.ncolblk, r % plan.ncolblk, b, lds.mean);
   } else {
     const int rr = r - n_mean;
-    gather_tile(g, K, V, Kc, Vc, idx, rr / nhg, rr % nhg, b, lds.gather);
+    gather_tile(g, K, V, Kc, Vc, idx, nullptr, rr / nhg, rr % nhg, b, lds.gather);
   }
 }
 
@@ -246,10 +322,13 @@ __global__ __launch_bounds__(kSubThreads) void subsample_kernel(
 // row groups each add every 32nd partial in double, then the 32 sums are added in order.
 constexpr int kFinalCols = 32;
 constexpr int kFinalGroups = 32;
+// With `cnt` (list variant) the number of averaged rows is the sum of the per-chunk counts
+// and is also written to nd_out[b]; otherwise it is the grid rule's g.n_dropped.
 __global__ __launch_bounds__(kFinalCols * kFinalGroups) void mean_final_kernel(
     Geom g, const float* __restrict__ partial, int nchunks, float* __restrict__ kmean,
-    float* __restrict__ vmean) {
+    float* __restrict__ vmean, const int32_t* __restrict__ cnt, int32_t* __restrict__ nd_out) {
   __shared__ double red[kFinalGroups][kFinalCols];
+  __shared__ int64_t nd_s;
   const int C = g.H * kHeadDim;
   const int cl = threadIdx.x % kFinalCols;
   const int rg = threadIdx.x / kFinalCols;
@@ -263,11 +342,21 @@ __global__ __launch_bounds__(kFinalCols * kFinalGroups) void mean_final_kernel(
     for (int k = rg; k < nchunks; k += kFinalGroups) s += (double)p[(int64_t)k * 2 * C];
   }
   red[rg][cl] = s;
+  if (threadIdx.x == 0) {
+    int64_t nd = g.n_dropped;
+    if (cnt) {
+      nd = 0;
+      for (int k = 0; k < nchunks; ++k) nd += cnt[(int64_t)b * nchunks + k];
+      if (blockIdx.x == 0) nd_out[b] = (int32_t)nd;
+    }
+    nd_s = nd;
+  }
   __syncthreads();
   if (rg == 0 && c < 2 * C) {
     double t = 0.0;
     for (int r = 0; r < kFinalGroups; ++r) t += red[r][cl];
-    const float m = (g.n_dropped > 0) ? (float)(t / (double)g.n_dropped) : 0.f;
+    const int64_t nd = nd_s;
+    const float m = (nd > 0) ? (float)(t / (double)nd) : 0.f;
     const int which = c / C, col = c % C;
     (which ? vmean : kmean)[(int64_t)b * C + col] = m;
   }
@@ -293,7 +382,181 @@ hipError_t launch_subsample(const Geom& g, const void* K, const void* V, void* K
   const int C = g.H * kHeadDim;
   dim3 grid2((unsigned)((2 * C + kFinalCols - 1) / kFinalCols), (unsigned)g.B);
   hipLaunchKernelGGL(mean_final_kernel, grid2, dim3(kFinalCols * kFinalGroups), 0, st, g,
-                     (const float*)workspace, plan.nchunks, kmean, vmean);
+                     (const float*)workspace, plan.nchunks, kmean, vmean, (const int32_t*)nullptr,
+                     (int32_t*)nullptr);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Caller-supplied kept lists (the token-selection ablation of the supplementary material)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bits_clear_kernel(uint32_t* __restrict__ bits, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+    bits[i] = 0u;
+}
+
+__global__ __launch_bounds__(256) void bits_set_kernel(const int32_t* __restrict__ list, int64_t M,
+                                                       int64_t NQ, int64_t nwords, int B,
+                                                       uint32_t* __restrict__ bits) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= M * B) return;
+  const int64_t b = i / M;
+  int64_t t = list[i];
+  t = t < 0 ? 0 : (t >= NQ ? NQ - 1 : t);
+  atomicOr(&bits[b * nwords + (t >> 5)], 1u << (t & 31));
+}
+
+__global__ __launch_bounds__(kSubThreads) void subsample_list_kernel(
+    Geom g, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    uint16_t* __restrict__ Kc, uint16_t* __restrict__ Vc, const int32_t* __restrict__ list,
+    const uint32_t* __restrict__ bits, int64_t nwords, float* __restrict__ partial,
+    int32_t* __restrict__ cnt, MeanPlan plan, int n_mean, int n_gather, int nhg) {
+  __shared__ __align__(16) SubLds lds;
+  const int per_b = n_mean + n_gather;
+  const int b = blockIdx.x / per_b;
+  const int r = blockIdx.x % per_b;
+  if (r < n_mean) {
+    mean_partial_bits(g, K, V, bits, nwords, partial, cnt, plan, r / plan.ncolblk,
+                      r % plan.ncolblk, b, lds.mean);
+  } else {
+    const int rr = r - n_mean;
+    gather_tile(g, K, V, Kc, Vc, nullptr, list, rr / nhg, rr % nhg, b, lds.gather);
+  }
+}
+
+// The list variant's mean role walks token ids, not dropped-row numbers.
+static MeanPlan mean_plan_list(const Geom& g) {
+  Geom t = g;
+  t.n_dropped = g.NQ;
+  return mean_plan(t);
+}
+
+int64_t list_words(const Geom& g) { return (g.NQ + 31) / 32; }
+
+size_t list_workspace_bytes(const Geom& g) {
+  const MeanPlan p = mean_plan_list(g);
+  const size_t partial = (size_t)g.B * p.nchunks * 2 * g.H * kHeadDim * sizeof(float);
+  return partial + (size_t)g.B * p.nchunks * sizeof(int32_t);
+}
+
+hipError_t launch_subsample_list(const Geom& g, const int32_t* list, const void* K, const void* V,
+                                 void* Kc, void* Vc, float* kmean, float* vmean, uint32_t* bits,
+                                 int32_t* nd_out, void* workspace, hipStream_t st) {
+  const MeanPlan plan = mean_plan_list(g);
+  const int64_t nwords = list_words(g);
+  const int nhg = (g.H + kHeadGroup - 1) / kHeadGroup;
+  const int64_t n_gather = (g.M_pad / kTileRows) * nhg;
+  const int64_t n_mean = (int64_t)plan.nchunks * plan.ncolblk;
+  const int64_t groups = (n_gather + n_mean) * g.B;
+  const int64_t set_groups = (g.M * g.B + 255) / 256;
+  if (groups > 0x7FFFFFFF || n_gather > 0x3FFFFFFF || set_groups > 0x7FFFFFFF)
+    return hipErrorInvalidConfiguration;
+  float* partial = (float*)workspace;
+  int32_t* cnt = (int32_t*)(partial + (size_t)g.B * plan.nchunks * 2 * g.H * kHeadDim);
+  (void)hipGetLastError();
+  const int64_t total_words = nwords * g.B;
+  const unsigned clear_groups = (unsigned)((total_words + 255) / 256 < 2048 ? (total_words + 255) / 256 : 2048);
+  hipLaunchKernelGGL(bits_clear_kernel, dim3(clear_groups), dim3(256), 0, st, bits, total_words);
+  hipLaunchKernelGGL(bits_set_kernel, dim3((unsigned)set_groups), dim3(256), 0, st, list, g.M, g.NQ,
+                     nwords, g.B, bits);
+  hipLaunchKernelGGL(subsample_list_kernel, dim3((unsigned)groups), dim3(kSubThreads), 0, st, g,
+                     (const uint16_t*)K, (const uint16_t*)V, (uint16_t*)Kc, (uint16_t*)Vc, list,
+                     (const uint32_t*)bits, nwords, partial, cnt, plan, (int)n_mean, (int)n_gather,
+                     nhg);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int C = g.H * kHeadDim;
+  dim3 grid2((unsigned)((2 * C + kFinalCols - 1) / kFinalCols), (unsigned)g.B);
+  hipLaunchKernelGGL(mean_final_kernel, grid2, dim3(kFinalCols * kFinalGroups), 0, st, g,
+                     (const float*)partial, plan.nchunks, kmean, vmean, (const int32_t*)cnt,
+                     nd_out);
+  return hipGetLastError();
+}
+
+// One wavefront per (batch, kept position): which token of the position's window serves as
+// key/value.  Special tokens and a whole-kept frame 0 map to themselves.
+__device__ inline uint32_t mix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7FEB352Du;
+  x ^= x >> 15;
+  x *= 0x846CA68Bu;
+  x ^= x >> 16;
+  return x;
+}
+
+__global__ __launch_bounds__(256) void select_kernel(Geom g, int rule, uint32_t seed32,
+                                                     const uint16_t* __restrict__ K,
+                                                     int32_t* __restrict__ list) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= g.M * g.B) return;  // uniform per wavefront
+  const int b = (int)(row / g.M);
+  const int64_t m = row % g.M;
+  // position m -> (frame, j) exactly as the grid rule numbers its kept rows
+  int64_t frame;
+  int32_t j;
+  if (g.keep_first && m < g.L) {
+    if (lane == 0) list[row] = (int32_t)m;
+    return;
+  }
+  {
+    const uint32_t r = (uint32_t)(g.keep_first ? m - g.L : m);
+    frame = (g.keep_first ? 1 : 0) + (int64_t)(r / (uint32_t)g.rows_sub);
+    j = (int32_t)(r % (uint32_t)g.rows_sub);
+  }
+  if (j < g.P) {
+    if (lane == 0) list[row] = (int32_t)(frame * g.L + j);
+    return;
+  }
+  const int32_t win = j - g.P;  // row-major window number inside the frame
+  const int32_t row0 = (win / g.kw) * g.s_h;
+  const int32_t col0 = (win % g.kw) * g.s_w;
+  const int32_t wrows = min(g.s_h, g.n_h - row0);
+  const int32_t wcols = min(g.s_w, g.n_w - col0);
+  const int32_t cells = wrows * wcols;
+  int32_t pick = 0;
+  if (rule == AGG_SELECT_RANDOM) {
+    uint32_t x = mix32(seed32 ^ ((uint32_t)(b * g.N + (int32_t)frame) * 0x85EBCA77u));
+    x = mix32(x ^ ((uint32_t)win * 0xC2B2AE3Du));
+    pick = (int32_t)(x % (uint32_t)cells);
+  } else if (rule == AGG_SELECT_HIGH || rule == AGG_SELECT_LOW) {
+    const int C = g.H * kHeadDim;
+    float best = 0.f;
+    for (int32_t c = 0; c < cells; ++c) {
+      const int64_t tok = frame * g.L + g.P + (int64_t)(row0 + c / wcols) * g.n_w + col0 + c % wcols;
+      const uint16_t* kr = K + ((int64_t)b * g.NQ + tok) * C;
+      float ss = 0.f;
+      for (int ch = lane * 8; ch < C; ch += 512) {
+        u32x4 v = *reinterpret_cast<const u32x4*>(kr + ch);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float lo = __uint_as_float(v[i] << 16), hi = __uint_as_float(v[i] & 0xFFFF0000u);
+          ss += lo * lo;
+          ss += hi * hi;
+        }
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+      const bool better = (rule == AGG_SELECT_HIGH) ? (ss > best) : (ss < best);
+      if (c == 0 || better) {
+        best = ss;
+        pick = c;
+      }
+    }
+  }
+  if (lane == 0)
+    list[row] = (int32_t)(frame * g.L + g.P + (int64_t)(row0 + pick / wcols) * g.n_w + col0 +
+                          pick % wcols);
+}
+
+hipError_t launch_select(const Geom& g, int rule, uint64_t seed, const void* K, int32_t* list,
+                         hipStream_t st) {
+  const int64_t groups = (g.M * g.B + 3) / 4;
+  if (groups > 0x7FFFFFFF) return hipErrorInvalidConfiguration;
+  const uint32_t seed32 = (uint32_t)seed ^ ((uint32_t)(seed >> 32) * 0x9E3779B1u);
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)groups), dim3(256), 0, st, g, rule, seed32,
+                     (const uint16_t*)K, list);
   return hipGetLastError();
 }
 

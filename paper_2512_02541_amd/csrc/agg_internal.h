@@ -120,7 +120,17 @@ hipError_t launch_subsample(const Geom& g, const void* K, const void* V, void* K
                             hipStream_t st);
 hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bias, const void* Q,
                        const void* K, const void* V, const void* Kc, const void* Vc,
-                       const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st);
+                       const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st,
+                       const uint32_t* kept_bits = nullptr, const int32_t* nd_dev = nullptr);
+
+// Caller-supplied kept lists: g.M / g.M_pad hold the list length.
+int64_t list_words(const Geom& g);               // uint32 words of one batch element's bitmap
+size_t list_workspace_bytes(const Geom& g);
+hipError_t launch_subsample_list(const Geom& g, const int32_t* list, const void* K, const void* V,
+                                 void* Kc, void* Vc, float* kmean, float* vmean, uint32_t* bits,
+                                 int32_t* nd_out, void* workspace, hipStream_t st);
+hipError_t launch_select(const Geom& g, int rule, uint64_t seed, const void* K, int32_t* list,
+                         hipStream_t st);
 
 hipError_t launch_layernorm(const void* x, const float* gamma, const float* beta, void* y,
                             int64_t rows, int C, float eps, hipStream_t st);

@@ -125,3 +125,54 @@ def decode_compact(flat: torch.Tensor, B: int, H: int, M: int, M_pad: int, which
     # [t(4)][g(2)][d(64)][e_hi(2)][e_lo(4)] ; row = 16t + 8e_hi + 4g + e_lo
     x = x.view(B, H, nt, 4, 2, 64, 2, 4).permute(0, 1, 2, 3, 6, 4, 7, 5)
     return x.reshape(B, H, M_pad, 64)
+
+
+@dataclass
+class ListBuffers:
+    shape: agg.agg_shape
+    M: int
+    M_pad: int
+    Kc: torch.Tensor
+    Vc: torch.Tensor
+    kmean: torch.Tensor
+    vmean: torch.Tensor
+    kept_bits: torch.Tensor
+    n_dropped: torch.Tensor
+    workspace: torch.Tensor
+    O: torch.Tensor
+    lse: torch.Tensor
+
+
+def list_forward(shape, kv_list, Q, K, V, poison=False) -> ListBuffers:
+    """The path over a caller's kept list: kv_list is a device int32 [B, M_list] tensor."""
+    B, H, D, NQ = shape.B, shape.H, shape.D, shape.NQ
+    M = kv_list.shape[1]
+    nbytes, m_pad = agg.agg_list_compact_bytes(shape, M)
+    dev = Q.device
+    mk = torch.empty
+    Kc = mk(nbytes // 2, dtype=torch.bfloat16, device=dev)
+    Vc = mk(nbytes // 2, dtype=torch.bfloat16, device=dev)
+    kmean = mk((B, H, D), dtype=torch.float32, device=dev)
+    vmean = mk((B, H, D), dtype=torch.float32, device=dev)
+    bits = mk((B, (NQ + 31) // 32), dtype=torch.int32, device=dev)
+    nd = mk((B,), dtype=torch.int32, device=dev)
+    ws = mk(agg.agg_list_workspace_bytes(shape), dtype=torch.uint8, device=dev)
+    O = mk((B, NQ, H, D), dtype=torch.bfloat16, device=dev)
+    lse = mk((B, H, NQ), dtype=torch.float32, device=dev)
+    if poison:
+        for t in (Kc, Vc, kmean, vmean, O, lse):
+            t.fill_(float("nan"))
+        bits.fill_(-1)
+        nd.fill_(-7)
+        ws.fill_(0xFF)
+    agg.agg_kv_subsample_list(shape, kv_list, M, K, V, Kc, Vc, kmean, vmean, bits, nd, ws, ws.numel())
+    agg.agg_global_attn_fwd_list(shape, M, Q, K, V, Kc, Vc, kmean, vmean, bits, nd, O, lse)
+    return ListBuffers(shape, M, m_pad, Kc, Vc, kmean, vmean, bits, nd, ws, O, lse)
+
+
+def select(shape, rule, seed, K):
+    """Device int32 [B, M] list chosen by `rule` (agg_select_kv_indices)."""
+    M, _ = agg.agg_kv_count(shape)
+    out = torch.full((shape.B, M), -1, dtype=torch.int32, device=K.device)
+    agg.agg_select_kv_indices(shape, rule, seed, K, out)
+    return out

@@ -370,3 +370,131 @@ def test_linear_and_layernorm_ragged_rows():
     want = blk.block(oshape(shape), blk.DENSE, inputs.bf16_bits(x), host)
     err = np.abs(y.double().cpu().numpy() - want)
     assert err.max() <= 6e-2 and err.mean() <= 4e-3, (err.max(), err.mean())
+
+
+# ----------------------------------------------------------------------------
+# Caller-supplied kept lists and the selection rules of the token-selection ablation
+# ----------------------------------------------------------------------------
+def lshape(s):
+    from oracle import list_oracle  # noqa: F401  (same field names as the C oracle's Shape)
+    return oshape(s)
+
+
+def check_list_case(shape, lst, q, k, v, rows=None, what=""):
+    """Runs the list path and checks every product against the list oracle."""
+    from oracle import list_oracle as lo
+
+    say("list case %s: B=%d N=%d grid=%dx%d P=%d H=%d M_list=%d flags=%d" % (
+        what, shape.B, shape.N, shape.n_h, shape.n_w, shape.n_special, shape.H, lst.shape[1],
+        shape.flags))
+    buf = harness.list_forward(shape, lst, q, k, v, poison=True)
+    torch.cuda.synchronize()
+    host_list = lst.cpu().numpy()
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    B, H, NQ, M = shape.B, shape.H, shape.NQ, lst.shape[1]
+    # compacted copies: row m of batch b is token list[b, m], bit for bit; padding zero
+    got_k = inputs.bf16_bits(harness.decode_compact(buf.Kc, B, H, M, buf.M_pad, "k"))
+    got_v = inputs.bf16_bits(harness.decode_compact(buf.Vc, B, H, M, buf.M_pad, "v"))
+    k4, v4 = kb.reshape(B, NQ, H, 64), vb.reshape(B, NQ, H, 64)
+    for b in range(B):
+        assert (got_k[b, :, :M] == k4[b, host_list[b]].transpose(1, 0, 2)).all(), "Kc differs"
+        assert (got_v[b, :, :M] == v4[b, host_list[b]].transpose(1, 0, 2)).all(), "Vc differs"
+    assert (got_k[:, :, M:] == 0).all() and (got_v[:, :, M:] == 0).all()
+    # membership bitmap
+    words = buf.kept_bits.cpu().numpy().view(np.uint32)
+    for b in range(B):
+        want = np.zeros(words.shape[1] * 32, dtype=bool)
+        want[host_list[b]] = True
+        got = ((words[b][:, None] >> np.arange(32, dtype=np.uint32)[None, :]) & 1).astype(bool).ravel()
+        assert (got == want).all(), "kept_bits differ"
+    if rows is None:
+        rows = np.arange(NQ, dtype=np.int64)
+    want_o, want_lse, km, vm, nd = lo.attn_rows(lshape(shape), host_list, qb, kb, vb, rows)
+    assert (buf.n_dropped.cpu().numpy() == nd).all(), (buf.n_dropped.cpu().numpy(), nd)
+    gk = buf.kmean.cpu().numpy().astype(np.float64)
+    gv = buf.vmean.cpu().numpy().astype(np.float64)
+    assert (np.abs(gk - km) <= 1e-6 + 1e-5 * np.abs(km)).all(), np.abs(gk - km).max()
+    assert (np.abs(gv - vm) <= 1e-6 + 1e-5 * np.abs(vm)).all(), np.abs(gv - vm).max()
+    check_output(buf.O, buf.lse, want_o, want_lse, rows, what)
+    return buf
+
+
+@pytest.mark.parametrize("keep_first", [0, 1])
+def test_selection_rules_match_oracle(keep_first):
+    from oracle import list_oracle as lo
+
+    shape = agg.make_shape(2, 3, 7, 8, 5, 4, 64, 3, 3, keep_first)
+    q, k, v = inputs.iid_qkv(2, shape.NQ, 4, 64, seed=700 + keep_first, device="cuda")
+    kb = inputs.bf16_bits(k)
+    first = harness.select(shape, agg.AGG_SELECT_FIRST, 0, k).cpu().numpy()
+    assert (first == agg.agg_kv_indices_host(shape)[None, :]).all()
+    for seed in (0, 77, (5 << 32) + 9):
+        got = harness.select(shape, agg.AGG_SELECT_RANDOM, seed, k).cpu().numpy()
+        want, _ = lo.select(lshape(shape), lo.RANDOM, seed, None)
+        assert (got == want).all(), seed
+    for rule, orule in ((agg.AGG_SELECT_HIGH, lo.HIGH), (agg.AGG_SELECT_LOW, lo.LOW)):
+        got = harness.select(shape, rule, 0, k).cpu().numpy()
+        want, cands = lo.select(lshape(shape), orule, 0, kb)
+        # the kernel ranks float32 sums of squares: where it differs from the float64 choice the
+        # two magnitudes must agree to float32 rounding of a 256-term sum
+        for b, m in zip(*np.nonzero(got != want)):
+            cells, mags = cands[b][m]
+            assert got[b, m] in cells
+            assert abs(mags[cells.index(got[b, m])] - mags[cells.index(want[b, m])]) <= \
+                1e-5 * abs(mags[cells.index(want[b, m])])
+        assert (got != want).mean() < 0.01
+
+
+@pytest.mark.parametrize("rule", [0, 1, 2, 3])
+@pytest.mark.parametrize("flags", [0, 3])
+def test_list_path_on_selected_lists(rule, flags):
+    shape = agg.make_shape(2, 3, 9, 7, 5, 3, 64, 2, 2, 1, flags=flags)
+    q, k, v = inputs.iid_qkv(2, shape.NQ, 3, 64, seed=710 + rule, device="cuda")
+    lst = harness.select(shape, rule, 31, k)
+    check_list_case(shape, lst, q, k, v, what="rule %d" % rule)
+
+
+def test_list_first_rule_agrees_with_grid_path(tiny_qkv):
+    w, (q, k, v) = tiny_qkv
+    shape = harness.shape_of(w)
+    lst = harness.select(shape, agg.AGG_SELECT_FIRST, 0, k)
+    a = harness.list_forward(shape, lst, q, k, v)
+    b = harness.sga_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    assert torch.equal(a.Kc.view(torch.int16), b.Kc.view(torch.int16))
+    assert torch.equal(a.Vc.view(torch.int16), b.Vc.view(torch.int16))
+    assert int(a.n_dropped[0]) == b.n_dropped
+    # the two mean reductions group their float32 partial sums differently
+    assert (a.kmean - b.kmean).abs().max() < 1e-6
+    assert (a.O.float() - b.O.float()).abs().max() <= 2.0 ** -7
+    assert (a.lse - b.lse).abs().max() < 1e-5
+
+
+def test_list_arbitrary_entries():
+    """Different lists per batch element, in random order, one leaving out special tokens,
+    one shorter than a tile of 64, and a list with a repeated token."""
+    from oracle import list_oracle as lo  # noqa: F401
+
+    shape = agg.make_shape(2, 2, 6, 5, 3, 2, 64, 2, 2, 0)
+    NQ = shape.NQ
+    q, k, v = inputs.iid_qkv(2, NQ, 2, 64, seed=720, device="cuda")
+    rng = np.random.default_rng(3)
+    for M in (40, 64, 65):
+        lists = np.stack([rng.choice(NQ, M, replace=False) for _ in range(2)]).astype(np.int32)
+        check_list_case(shape, torch.from_numpy(lists).cuda(), q, k, v, what="random M=%d" % M)
+    repeated = np.stack([rng.choice(NQ, 50, replace=True) for _ in range(2)]).astype(np.int32)
+    assert len(set(repeated[0].tolist())) < 50
+    check_list_case(shape, torch.from_numpy(repeated).cuda(), q, k, v, what="repeated ids")
+    everything = np.stack([rng.permutation(NQ), rng.permutation(NQ)]).astype(np.int32)
+    buf = check_list_case(shape, torch.from_numpy(everything).cuda(), q, k, v, what="all tokens")
+    assert (buf.n_dropped == 0).all()
+
+
+def test_list_full_size_random_rule():
+    """100 frames: one random token per window, sampled query rows against the oracle."""
+    w = inputs.WORKLOADS["f100"]
+    shape = harness.shape_of(w)
+    q, k, v = inputs.make_qkv(w, "cuda")
+    lst = harness.select(shape, agg.AGG_SELECT_RANDOM, 2024, k)
+    rows = np.array([0, 1373, 1374, 1379, 1380, 70000, 137399, 98765], dtype=np.int64)
+    check_list_case(shape, lst, q, k, v, rows=rows, what="f100 random")

@@ -554,3 +554,141 @@ def test_block_oracle_pieces_and_composition():
             o, _ = orc.dense_rows(shape, xn, xn, xn, rows)
         o = blk.from_bf16_bits(blk.to_bf16_bits(o)).reshape(1, shape.NQ, C)
         assert np.array_equal(y, blk.from_bf16_bits(blk.to_bf16_bits(x + o)))
+
+
+# ----------------------------------------------------------------------------
+# List-driven oracle (token-selection ablation of the supplementary material)
+# ----------------------------------------------------------------------------
+def _list_shape(**kw):
+    return small_shape(**kw)
+
+
+@pytest.mark.parametrize("keep_first", [0, 1])
+def test_list_first_rule_is_the_grid_rule(keep_first):
+    from oracle import list_oracle as lo
+
+    shape = _list_shape(B=2, keep_first_frame=keep_first)
+    q, k, v = draw(shape, seed=61)
+    lst, _ = lo.select(shape, lo.FIRST, 0, None)
+    assert (lst == orc.kept_indices(shape)[None, :]).all()
+    rows = np.arange(shape.NQ)
+    O, lse, km, vm, nd = lo.attn_rows(shape, lst, bits(q), bits(k), bits(v), rows)
+    res = orc.sga(shape, bits(q), bits(k), bits(v))
+    assert (nd == res["n_dropped"]).all()
+    assert np.abs(O - res["O"]).max() < 1e-11
+    assert np.abs(lse - res["lse"]).max() < 1e-11
+    assert np.abs(km - res["kmean"]).max() < 1e-12 and np.abs(vm - res["vmean"]).max() < 1e-12
+
+
+def test_list_of_all_tokens_is_dense_attention_and_order_is_irrelevant():
+    from oracle import list_oracle as lo
+
+    shape = _list_shape()
+    q, k, v = draw(shape, seed=62)
+    rows = np.arange(shape.NQ)
+    rng = np.random.default_rng(5)
+    everything = rng.permutation(shape.NQ).astype(np.int32)[None, :]
+    O, lse, _, _, nd = lo.attn_rows(shape, everything, bits(q), bits(k), bits(v), rows)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        q.double().permute(0, 2, 1, 3), k.double().permute(0, 2, 1, 3), v.double().permute(0, 2, 1, 3),
+        scale=shape.scale).permute(0, 2, 1, 3).numpy()
+    assert nd[0] == 0
+    assert np.abs(O - want).max() < 1e-11
+    # a shuffled subset gives the same result as the sorted one
+    sub = np.sort(rng.choice(shape.NQ, size=shape.NQ // 3, replace=False)).astype(np.int32)
+    a = lo.attn_rows(shape, sub[None, :], bits(q), bits(k), bits(v), rows)
+    b = lo.attn_rows(shape, rng.permutation(sub)[None, :], bits(q), bits(k), bits(v), rows)
+    assert np.abs(a[0] - b[0]).max() < 1e-12 and np.abs(a[1] - b[1]).max() < 1e-12
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+def test_list_attention_equals_masked_dense_attention(flags):
+    """Random lists that contain every special token (so that 'unlisted' and 'unlisted patch'
+    coincide) against the masked dense reference; batch elements get different lists."""
+    from oracle import list_oracle as lo
+
+    shape = _list_shape(B=2, flags=flags)
+    q, k, v = draw(shape, seed=63 + flags)
+    rng = np.random.default_rng(11 + flags)
+    L, P = shape.L, shape.n_special
+    special = np.array([f * L + p for f in range(shape.N) for p in range(P)])
+    patches = np.array([t for t in range(shape.NQ) if t % L >= P])
+    n_pick = 17
+    lists = np.stack([np.concatenate([special, rng.choice(patches, n_pick, replace=False)])
+                      for _ in range(shape.B)]).astype(np.int32)
+    rows = np.arange(shape.NQ)
+    O, lse, _, _, nd = lo.attn_rows(shape, lists, bits(q), bits(k), bits(v), rows)
+    assert (nd == len(patches) - n_pick).all()
+    for b in range(shape.B):
+        kept = np.zeros(shape.NQ, dtype=bool)
+        kept[lists[b]] = True
+        one = orc.Shape(**{**shape.__dict__, "B": 1})
+        wo, wl, _ = masked_dense_reference(one, q[b:b + 1], k[b:b + 1], v[b:b + 1], kept,
+                                           bool(flags & 1), bool(flags & 2))
+        assert np.abs(O[b] - wo[0]).max() < 1e-11
+        assert np.abs(lse[b] - wl[0]).max() < 1e-11
+
+
+def test_list_unlisted_special_token_gets_self_term_but_is_not_averaged():
+    from oracle import list_oracle as lo
+
+    shape = _list_shape(N=1, n_h=2, n_w=2, n_special=1, H=1, keep_first_frame=0)
+    q, k, v = draw(shape, seed=64)          # tokens: 0 special, 1..4 patches
+    lst = np.array([[1, 3]], dtype=np.int32)
+    O, lse, km, vm, nd = lo.attn_rows(shape, lst, bits(q), bits(k), bits(v), [0, 2])
+    kd, vd, qd = (t.double().numpy()[0, :, 0] for t in (k, v, q))
+    assert nd[0] == 2 and np.allclose(km[0, 0], (kd[2] + kd[4]) / 2, atol=1e-15)
+    for r, i in enumerate((0, 2)):
+        cols_k = np.stack([kd[1], kd[3], kd[i], (kd[2] + kd[4]) / 2])
+        cols_v = np.stack([vd[1], vd[3], vd[i], (vd[2] + vd[4]) / 2])
+        z = shape.scale * cols_k @ qd[i]
+        p = np.exp(z - z.max())
+        p /= p.sum()
+        assert np.abs(O[0, r, 0] - p @ cols_v).max() < 1e-13
+
+
+def test_selection_rules_pick_inside_their_window():
+    from oracle import list_oracle as lo
+
+    shape = _list_shape(B=2, N=4, n_h=7, n_w=8, s_h=3, s_w=3, keep_first_frame=1)
+    q, k, v = draw(shape, seed=65)
+    grid = orc.kept_indices(shape)
+    L, P = shape.L, shape.n_special
+    kd = k.double().numpy().reshape(shape.B, shape.NQ, -1)
+    mag = (kd * kd).sum(-1)
+    for rule in (lo.RANDOM, lo.HIGH, lo.LOW):
+        lst, _ = lo.select(shape, rule, 1234, bits(k))
+        assert lst.shape == (shape.B, len(grid))
+        for b in range(shape.B):
+            assert len(set(lst[b].tolist())) == len(grid)   # one distinct token per position
+            for m, g in enumerate(grid):
+                t = int(lst[b, m])
+                if g % L < P or g // L == 0:
+                    assert t == g                             # special tokens, reference frame
+                    continue
+                assert t // L == g // L
+                gr, gc = divmod(g % L - P, shape.n_w)
+                tr, tc = divmod(t % L - P, shape.n_w)
+                assert gr <= tr < min(gr + shape.s_h, shape.n_h)
+                assert gc <= tc < min(gc + shape.s_w, shape.n_w)
+                if rule != lo.RANDOM:                         # explicit loop over the window
+                    window = [g // L * L + P + r * shape.n_w + c
+                              for r in range(gr, min(gr + shape.s_h, shape.n_h))
+                              for c in range(gc, min(gc + shape.s_w, shape.n_w))]
+                    best = max(window, key=lambda x: mag[b, x]) if rule == lo.HIGH else \
+                        min(window, key=lambda x: mag[b, x])
+                    assert mag[b, t] == mag[b, best]
+
+
+def test_random_rule_is_uniform_over_cells_and_depends_on_seed():
+    from oracle import list_oracle as lo
+
+    counts = np.zeros(4)
+    for w in range(4000):
+        counts[lo.random_cell(99, 0, 1 + w % 7, w, 8, 4)] += 1
+    assert (np.abs(counts - 1000) < 130).all(), counts          # ~4.7 sigma of a fair draw
+    a = [lo.random_cell(1, 0, 1, w, 8, 9) for w in range(64)]
+    b = [lo.random_cell(2, 0, 1, w, 8, 9) for w in range(64)]
+    c = [lo.random_cell(1 + (1 << 32), 0, 1, w, 8, 9) for w in range(64)]
+    assert a != b and a != c
+    assert all(0 <= x < 9 for x in a)
