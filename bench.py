@@ -240,7 +240,29 @@ def run_sweep(args, log):
             sigma, keep_first, flags, buf.M, ms_g, ms_a))
         del buf
         torch.cuda.empty_cache()
-    print(json.dumps({"sweep": args.workload, "NQ": w.NQ, "rows": rows}))
+    # token-selection ablation (supplementary material): one token per window chosen at random
+    # or by feature magnitude, run through the list-driven entry points
+    shape = harness.shape_of(w)
+    M, _ = agg.agg_kv_count(shape)
+    list_rows = []
+    for rule, name in ((agg.AGG_SELECT_FIRST, "first"), (agg.AGG_SELECT_RANDOM, "random"),
+                       (agg.AGG_SELECT_HIGH, "high"), (agg.AGG_SELECT_LOW, "low")):
+        lst = torch.empty((w.B, M), dtype=torch.int32, device="cuda")
+        ms_sel, _ = time_events(lambda: agg.agg_select_kv_indices(shape, rule, 7, k, lst), args.steps, 1)
+        lb = harness.list_forward(shape, lst, q, k, v)
+        ms_sub, _ = time_events(lambda: agg.agg_kv_subsample_list(
+            shape, lst, M, k, v, lb.Kc, lb.Vc, lb.kmean, lb.vmean, lb.kept_bits, lb.n_dropped,
+            lb.workspace, lb.workspace.numel()), args.steps, 1)
+        ms_att, _ = time_events(lambda: agg.agg_global_attn_fwd_list(
+            shape, M, q, k, v, lb.Kc, lb.Vc, lb.kmean, lb.vmean, lb.kept_bits, lb.n_dropped, lb.O,
+            None), args.steps, 1)
+        list_rows.append({"rule": name, "M": M, "ms_select": ms_sel, "ms_subsample_list": ms_sub,
+                          "ms_attn_list": ms_att})
+        log("rule %s: select %.3f ms, list gather+mean %.3f ms, attn %.2f ms" % (
+            name, ms_sel, ms_sub, ms_att))
+        del lb, lst
+        torch.cuda.empty_cache()
+    print(json.dumps({"sweep": args.workload, "NQ": w.NQ, "rows": rows, "selection_rules": list_rows}))
     return 0
 
 
