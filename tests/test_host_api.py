@@ -147,6 +147,50 @@ def test_error_paths_before_any_launch():
     assert den(ctypes.byref(good), fake, fake, fake, fake, None, fake, dws - 1, None) == -5
     assert den(ctypes.byref(good), fake, fake, fake, odd, None, fake, dws, None) == -4
 
+    # frame attention and the block: same validation before any launch
+    fws = agg.agg_frame_workspace_bytes(good)
+    assert fws == 2 * 2 * 16 * 320 * 64 * 2  # 2 frames of 261 tokens, each padded to 320 rows
+    fr = lib.agg_frame_attn_fwd
+    assert fr(ctypes.byref(good), fake, fake, fake, fake, None, None, fws, None) == -1
+    assert fr(ctypes.byref(good), fake, fake, fake, fake, None, fake, fws - 1, None) == -5
+    w = agg.agg_block_weights(0x1000, 0x1000, 1e-6, 0x1000, 0x1000, 0x1000, 0x1000, None, None,
+                              None, None)
+    blk = lib.agg_global_block_fwd
+    for mode in (agg.AGG_BLOCK_SGA, agg.AGG_BLOCK_FRAME, agg.AGG_BLOCK_DENSE):
+        bws = agg.agg_block_workspace_bytes(good, mode)
+        assert bws > 5 * 522 * 1024 * 2
+        other = ctypes.c_void_p(0x2000)
+        assert blk(ctypes.byref(good), mode, ctypes.byref(w), fake, other, fake, bws - 1, None) == -5
+        assert blk(ctypes.byref(good), mode, ctypes.byref(w), None, other, fake, bws, None) == -1
+        assert blk(ctypes.byref(good), mode, None, fake, other, fake, bws, None) == -1
+        assert blk(ctypes.byref(good), mode, ctypes.byref(w), fake, fake, fake, bws, None) == -2  # y aliases x
+    assert agg.agg_block_workspace_bytes(good, 7) == 0
+    assert blk(ctypes.byref(good), 7, ctypes.byref(w), fake, fake, fake, 1 << 40, None) == -2
+
+    # caller-supplied lists
+    nbytes, m_pad = agg.agg_list_compact_bytes(good, 65)
+    assert (nbytes, m_pad) == (1 * 16 * 128 * 64 * 2, 128)
+    sz, mp = ctypes.c_size_t(0), ctypes.c_int64(0)
+    assert lib.agg_list_compact_bytes(ctypes.byref(good), 0, ctypes.byref(sz), ctypes.byref(mp)) == -2
+    lws = agg.agg_list_workspace_bytes(good)
+    assert lws > 0
+    sel = lib.agg_select_kv_indices
+    assert sel(ctypes.byref(good), 9, 0, fake, fake, None) == -2
+    assert sel(ctypes.byref(good), agg.AGG_SELECT_HIGH, 0, None, fake, None) == -1
+    assert sel(ctypes.byref(good), agg.AGG_SELECT_RANDOM, 0, None, None, None) == -1
+    sl = lib.agg_kv_subsample_list
+    assert sl(ctypes.byref(good), fake, 65, fake, fake, fake, fake, fake, fake, fake, fake, fake,
+              lws - 1, None) == -5
+    assert sl(ctypes.byref(good), None, 65, fake, fake, fake, fake, fake, fake, fake, fake, fake,
+              lws, None) == -1
+    assert sl(ctypes.byref(good), fake, 0, fake, fake, fake, fake, fake, fake, fake, fake, fake,
+              lws, None) == -2
+    al = lib.agg_global_attn_fwd_list
+    assert al(ctypes.byref(good), 65, fake, fake, fake, fake, fake, fake, fake, None, fake, fake,
+              None, None) == -1
+    assert al(ctypes.byref(good), 65, fake, fake, fake, fake, odd, fake, fake, fake, fake, fake,
+              None, None) == -4
+
 
 def test_missing_library_is_an_error(monkeypatch):
     monkeypatch.setattr(agg, "_lib", None)
