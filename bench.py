@@ -192,10 +192,23 @@ def run_only(args, log):
         return 0
     w = inputs.WORKLOADS[args.workload]
     shape = harness.shape_of(w)
-    q, k, v = inputs.make_qkv(w, "cuda")
+    if args.data == "zeros":      # same launches on all-zero tensors: isolates the effect of the
+        q = k = v = torch.zeros((w.B, w.NQ, w.H, w.D), dtype=torch.bfloat16, device="cuda")  # chip's power management
+    elif args.data == "iid":
+        q, k, v = inputs.iid_qkv(w.B, w.NQ, w.H, w.D, w.seed, "cuda")
+    else:
+        q, k, v = inputs.make_qkv(w, "cuda")
     buf = harness.alloc(shape, "cuda")
     harness.subsample(buf, k, v)
     torch.cuda.synchronize()
+    if args.only == "attn" and args.steps >= 5:
+        ms, mn = time_events(lambda: harness.attend(buf, q, k, v), args.steps, 2)
+        fl = sga_flops(w.NQ, buf.M, w.H, w.D)
+        print(json.dumps({"only": "attn", "workload": args.workload, "data": args.data,
+                          "launches": args.steps + 2, "ms_attn": ms, "ms_attn_min": mn,
+                          "tflops_attn": fl / (ms * 1e-3) / 1e12,
+                          "frac_peak": fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}))
+        return 0
     if args.only == "dense":
         nws = agg.agg_dense_workspace_bytes(shape)
         ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
@@ -368,6 +381,9 @@ def main():
     ap.add_argument("--layers", type=int, default=12)
     ap.add_argument("--t-early", type=int, default=4,
                     help="with --block: leading blocks run as per-frame attention")
+    ap.add_argument("--data", choices=["structured", "iid", "zeros"], default="structured",
+                    help="with --only: values of Q/K/V (zeros shows what the same instruction stream "
+                         "reaches when the operands do not toggle)")
     ap.add_argument("--only", choices=["attn", "gather", "dense", "copy"], default=None,
                     help="profiling aid: launch just this piece `steps` times (for rocprofv3 runs)")
     args = ap.parse_args()

@@ -386,9 +386,11 @@ int agg_global_block_fwd(const agg_shape* shape, int mode, const agg_block_weigh
 
   if (launch_layernorm(x, w->ln_gamma, w->ln_beta, xn, rows, C, w->ln_eps, st) != hipSuccess)
     return AGG_ERR_LAUNCH;
-  if (launch_linear(xn, w->w_q, w->b_q, nullptr, Q, rows, C, C, st) != hipSuccess ||
-      launch_linear(xn, w->w_k, w->b_k, nullptr, K, rows, C, C, st) != hipSuccess ||
-      launch_linear(xn, w->w_v, w->b_v, nullptr, V, rows, C, C, st) != hipSuccess)
+  const LinearOuts qkv = {{(const uint16_t*)w->w_q, (const uint16_t*)w->w_k, (const uint16_t*)w->w_v},
+                          {w->b_q, w->b_k, w->b_v},
+                          {(uint16_t*)Q, (uint16_t*)K, (uint16_t*)V},
+                          3};
+  if (launch_linear(xn, qkv, nullptr, rows, C, C, st) != hipSuccess)
     return AGG_ERR_LAUNCH;
   if (mode == AGG_BLOCK_SGA) {
     const size_t means = align256((size_t)shape->B * shape->H * kHeadDim * sizeof(float));
@@ -407,7 +409,11 @@ int agg_global_block_fwd(const agg_shape* shape, int mode, const agg_block_weigh
     rc = agg_dense_global_attn_fwd(shape, Q, K, V, A, nullptr, aws, p.attn_ws, hip_stream);
   }
   if (rc != AGG_OK) return rc;
-  if (launch_linear(A, w->w_o, w->b_o, x, y, rows, C, C, st) != hipSuccess) return AGG_ERR_LAUNCH;
+  const LinearOuts out = {{(const uint16_t*)w->w_o, nullptr, nullptr},
+                          {w->b_o, nullptr, nullptr},
+                          {(uint16_t*)y, nullptr, nullptr},
+                          1};
+  if (launch_linear(A, out, x, rows, C, C, st) != hipSuccess) return AGG_ERR_LAUNCH;
   return AGG_OK;
 }
 

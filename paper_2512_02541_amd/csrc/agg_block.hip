@@ -109,17 +109,35 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
 // transposed (W rows as the MFMA A operand) so that a lane ends up with four
 // consecutive output channels of one token: 8-byte stores.
 // Requires K % 64 == 0 and N % 8 == 0.
+//
+// One launch serves up to three weight matrices applied to the same input (the Q, K and V
+// projections): their output tiles of one token tile are neighbours in the launch order and
+// run on the same XCD, so a token tile is fetched from HBM once and then served by that
+// XCD's L2 to all of them.
 // ---------------------------------------------------------------------------
 constexpr int kGemmThreads = 256;
 constexpr int kTM = 128, kTN = 128, kTK = 64;
+constexpr int kGemmXcds = 8;
 
 __device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ (row & 7)); }
 
 __global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
-    const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, const float* __restrict__ bias,
-    const uint16_t* __restrict__ R, uint16_t* __restrict__ Y, int64_t rows, int N, int K) {
+    const uint16_t* __restrict__ A, LinearOuts outs, const uint16_t* __restrict__ R, int64_t rows,
+    int N, int K, int gm, int gn) {
   __shared__ __align__(16) u32x4 sA[2][kTM * 8];
   __shared__ __align__(16) u32x4 sW[2][kTN * 8];
+  // workgroup id -> (token tile, output tile): consecutive ids go to consecutive XCDs; an XCD
+  // walks all output tiles of one token tile before it moves to its next token tile
+  const int xcd = blockIdx.x % kGemmXcds;
+  const int seq = blockIdx.x / kGemmXcds;
+  const int per_m = gn * outs.count;
+  const int mt = (seq / per_m) * kGemmXcds + xcd;
+  if (mt >= gm) return;  // uniform for the workgroup, before any barrier
+  const int nt_all = seq % per_m;
+  const int which = nt_all / gn;
+  const uint16_t* __restrict__ W = outs.W[which];
+  const float* __restrict__ bias = outs.bias[which];
+  uint16_t* __restrict__ Y = outs.Y[which];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -127,8 +145,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
   const int g2 = lane >> 5;
   const int wm = (wave & 1) * 64;   // this wavefront's 64 token rows inside the tile
   const int wn = (wave >> 1) * 64;  // and its 64 output channels
-  const int64_t m0 = (int64_t)blockIdx.x * kTM;
-  const int n0 = blockIdx.y * kTN;
+  const int64_t m0 = (int64_t)mt * kTM;
+  const int n0 = (nt_all % gn) * kTN;
 
   // staging: 128 rows x 8 chunks per operand = 1024 chunks, 4 per thread
   u32x4 ra[4], rw[4];
@@ -227,16 +245,16 @@ hipError_t launch_layernorm(const void* x, const float* gamma, const float* beta
   return hipGetLastError();
 }
 
-hipError_t launch_linear(const void* A, const void* W, const float* bias, const void* R, void* Y,
-                         int64_t rows, int N, int K, hipStream_t st) {
-  if (K % kTK != 0 || N % 8 != 0) return hipErrorInvalidValue;
+hipError_t launch_linear(const void* A, const LinearOuts& outs, const void* R, int64_t rows, int N,
+                         int K, hipStream_t st) {
+  if (K % kTK != 0 || N % 8 != 0 || outs.count < 1 || outs.count > 3) return hipErrorInvalidValue;
   const int64_t gm = (rows + kTM - 1) / kTM;
   const int gn = (N + kTN - 1) / kTN;
-  if (gm > 0x7FFFFFFF || gn > 65535) return hipErrorInvalidConfiguration;
+  const int64_t groups = (gm + kGemmXcds - 1) / kGemmXcds * kGemmXcds * gn * outs.count;
+  if (groups > 0x7FFFFFFF) return hipErrorInvalidConfiguration;
   (void)hipGetLastError();
-  hipLaunchKernelGGL(linear_kernel, dim3((unsigned)gm, (unsigned)gn), dim3(kGemmThreads), 0, st,
-                     (const uint16_t*)A, (const uint16_t*)W, bias, (const uint16_t*)R, (uint16_t*)Y,
-                     rows, N, K);
+  hipLaunchKernelGGL(linear_kernel, dim3((unsigned)groups), dim3(kGemmThreads), 0, st,
+                     (const uint16_t*)A, outs, (const uint16_t*)R, rows, N, K, (int)gm, gn);
   return hipGetLastError();
 }
 

@@ -134,9 +134,16 @@ hipError_t launch_select(const Geom& g, int rule, uint64_t seed, const void* K, 
 
 hipError_t launch_layernorm(const void* x, const float* gamma, const float* beta, void* y,
                             int64_t rows, int C, float eps, hipStream_t st);
-// Y[rows, N] = A[rows, K] W[N, K]^T + bias (+ R); bf16 tensors, float bias (may be null)
-hipError_t launch_linear(const void* A, const void* W, const float* bias, const void* R, void* Y,
-                         int64_t rows, int N, int K, hipStream_t st);
+// Y_i[rows, N] = A[rows, K] W_i[N, K]^T + bias_i (+ R) for i < count (1..3 weight matrices
+// applied to the same input in one launch); bf16 tensors, float bias (may be null)
+struct LinearOuts {
+  const uint16_t* W[3];
+  const float* bias[3];
+  uint16_t* Y[3];
+  int count;
+};
+hipError_t launch_linear(const void* A, const LinearOuts& outs, const void* R, int64_t rows, int N,
+                         int K, hipStream_t st);
 
 int mean_chunks(const Geom& g);  // number of partial-sum blocks the mean kernel uses
 
