@@ -212,3 +212,29 @@ def test_decode_compact_inverts_the_documented_layout():
                 flat[fn(m, d)] = m * 64 + d
         dec = harness.decode_compact(flat, 1, 1, M_pad, M_pad, which)
         assert torch.equal(dec.reshape(-1), torch.arange(M_pad * 64, dtype=torch.float32))
+
+
+def test_product_and_oracle_share_nothing():
+    """The library, its binding and the benchmark's product path never reach into oracle/, and
+    the oracle never reaches into the package (only the input generators serve both)."""
+    pkg = os.path.join(ROOT, "paper_2512_02541_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for name in files:
+            if not name.endswith((".py", ".cpp", ".hip", ".h")):
+                continue
+            text = open(os.path.join(dirpath, name)).read()
+            assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), name
+            assert "sga_oracle" not in text and "block_oracle" not in text and \
+                "list_oracle" not in text, name
+    for name in os.listdir(os.path.join(ROOT, "oracle")):
+        if name.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", name)).read()
+            assert "paper_2512_02541_amd" not in text and "agg.h" not in text and \
+                "agg_internal" not in text, name
+    # bench.py touches the oracle only inside its CPU-baseline leg
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    for m in re.finditer(r"^\s*(from|import)\s+oracle\b.*$", bench, flags=re.M):
+        last_def = re.findall(r"^def (\w+)\(", bench[:m.start()], flags=re.M)[-1]
+        assert last_def == "cpu_baseline", (m.group(0), last_def)
