@@ -16,7 +16,10 @@
 //   * K/V arrive in "fragment order" (agg.h): a 64-key tile is a linear 8 KiB
 //     copy into LDS and every MFMA A operand is one conflict-free 16-byte read.
 //     Three tiles are resident: the one in use, the next one (its first
-//     fragments are fetched a block ahead) and the one being written.
+//     fragments are fetched a block ahead) and the one being filled.  Tiles go
+//     global -> LDS without passing through registers (global_load_lds_dwordx4),
+//     one tile ahead; a wavefront waits for its own copies before the barrier
+//     that ends an iteration.
 //   * At head dimension 64 the vector ALU is as loaded as the matrix core (one
 //     exponential per 256 MFMA flops) and a wavefront issues in order, so the
 //     key loop is software-pipelined: while the matrix core runs K Q^T of block
@@ -78,6 +81,25 @@ __device__ inline void lds_barrier() {
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
+
+// Asynchronous copy of one 8 KiB tile (512 chunks of 16 bytes) global -> LDS without passing
+// through registers: each wavefront lands 64 consecutive chunks per instruction.
+__device__ inline void dma16(const u32x4* gsrc, uint32_t lds_wave_base) {
+  // M0 carries the wavefront's LDS base; lane i lands its 16 bytes at base + 16 i.  Written as
+  // assembly so that the compiler's wait-count pass does not serialise later LDS reads of
+  // OTHER buffers behind this copy; the loop waits for it explicitly before the barrier.
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gsrc), "s"(lds_wave_base)
+               : "memory", "m0");
+}
+__device__ inline void tile_to_lds(const u32x4* __restrict__ src, u32x4* dst, int tid, int wave) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)(dst + wave * 64)));
+  dma16(src + tid, base);
+  dma16(src + kAttnThreads + tid, base + kAttnThreads * 16);
+}
+__device__ inline void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 
 #define AGG_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a).h, (b).h, (c), 0, 0, 0)
 
@@ -283,29 +305,14 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
       la[qb][1] = 0.f;
     }
 
-    // stage tiles 0 and 1; keep tile 2 in registers
-    u32x4 pk0 = kc4[tid], pk1 = kc4[tid + kAttnThreads];
-    u32x4 pv0 = vc4[tid], pv1 = vc4[tid + kAttnThreads];
-    lds_k(0)[tid] = pk0;
-    lds_k(0)[tid + kAttnThreads] = pk1;
-    lds_v(0)[tid] = pv0;
-    lds_v(0)[tid + kAttnThreads] = pv1;
+    // tiles 0 and 1 -> LDS
+    tile_to_lds(kc4, lds_k(0), tid, wave);
+    tile_to_lds(vc4, lds_v(0), tid, wave);
     if (ntiles > 1) {
-      pk0 = kc4[kChunks + tid];
-      pk1 = kc4[kChunks + tid + kAttnThreads];
-      pv0 = vc4[kChunks + tid];
-      pv1 = vc4[kChunks + tid + kAttnThreads];
-      lds_k(1)[tid] = pk0;
-      lds_k(1)[tid + kAttnThreads] = pk1;
-      lds_v(1)[tid] = pv0;
-      lds_v(1)[tid + kAttnThreads] = pv1;
+      tile_to_lds(kc4 + kChunks, lds_k(1), tid, wave);
+      tile_to_lds(vc4 + kChunks, lds_v(1), tid, wave);
     }
-    if (ntiles > 2) {
-      pk0 = kc4[2 * kChunks + tid];
-      pk1 = kc4[2 * kChunks + tid + kAttnThreads];
-      pv0 = vc4[2 * kChunks + tid];
-      pv1 = vc4[2 * kChunks + tid + kAttnThreads];
-    }
+    wait_vm0();
     lds_barrier();
 
     // pipeline prologue: scores of block 0 and probabilities of its first query block
@@ -326,18 +333,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
     for (int t = 0; t + 1 < ntiles; ++t) {
       const int nxt = (cur == kLdsTiles - 1) ? 0 : cur + 1;
       const int wrt = (nxt == kLdsTiles - 1) ? 0 : nxt + 1;
-      if (t + 2 < ntiles) {  // tile t+2 -> the buffer tile t-1 has left
-        lds_k(wrt)[tid] = pk0;
-        lds_k(wrt)[tid + kAttnThreads] = pk1;
-        lds_v(wrt)[tid] = pv0;
-        lds_v(wrt)[tid + kAttnThreads] = pv1;
-        if (t + 3 < ntiles) {
-          const int64_t off = (int64_t)(t + 3) * kChunks + tid;
-          pk0 = kc4[off];
-          pk1 = kc4[off + kAttnThreads];
-          pv0 = vc4[off];
-          pv1 = vc4[off + kAttnThreads];
-        }
+      if (t + 2 < ntiles) {  // tile t+2 -> the buffer tile t-1 has left (barrier of t-1)
+        tile_to_lds(kc4 + (int64_t)(t + 2) * kChunks, lds_k(wrt), tid, wave);
+        tile_to_lds(vc4 + (int64_t)(t + 2) * kChunks, lds_v(wrt), tid, wave);
       }
       f32x16 Sn0, Sn1, Sm0;
       Frag P0b[2];
@@ -357,6 +355,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
       load_k_frags(lds_k(nxt), 1, l32, g2, a);
       pv8(v, P0b, P1, Oacc);
       exp16(Sm0, P0, la[0][0], la[0][1]);
+      wait_vm0();  // this wavefront's part of tile t+2 has landed
       lds_barrier();
       cur = nxt;
     }
