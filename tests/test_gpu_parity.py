@@ -498,3 +498,71 @@ def test_list_full_size_random_rule():
     lst = harness.select(shape, agg.AGG_SELECT_RANDOM, 2024, k)
     rows = np.array([0, 1373, 1374, 1379, 1380, 70000, 137399, 98765], dtype=np.int64)
     check_list_case(shape, lst, q, k, v, rows=rows, what="f100 random")
+
+
+def _capture(fn):
+    """Warm up fn on a side stream, capture it into a graph on that stream, return the graph."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fn()
+    return graph
+
+
+def test_hip_graph_replays_of_block_and_list_paths():
+    """Every launch of the multi-kernel entry points is capturable (they clear with kernels,
+    not memsets) and each replay reproduces the eager result bit for bit."""
+    shape = agg.make_shape(1, 3, 9, 7, 5, 4, 64, 2, 2, 1)
+    C = shape.H * 64
+    wts = inputs.block_weights(C, seed=11, device="cuda")
+    x = inputs.block_input(1, shape.NQ, C, seed=11, device="cuda")
+    for mode in (agg.AGG_BLOCK_SGA, agg.AGG_BLOCK_FRAME):
+        eager, _ = harness.block_forward(shape, mode, wts, x)
+        torch.cuda.synchronize()
+        cw = agg.make_block_weights(wts["ln_gamma"], wts["ln_beta"], wts["ln_eps"], wts["w_q"],
+                                    wts["w_k"], wts["w_v"], wts["w_o"], wts["b_q"], wts["b_k"],
+                                    wts["b_v"], wts["b_o"])
+        nws = agg.agg_block_workspace_bytes(shape, mode)
+        ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        graph = _capture(lambda: agg.agg_global_block_fwd(shape, mode, cw, x, y, ws, nws))
+        for replay in range(3):
+            y.fill_(float("nan"))
+            ws.fill_(0xFF)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y.view(torch.int16), eager.view(torch.int16)), (mode, replay)
+
+    q, k, v = inputs.iid_qkv(1, shape.NQ, shape.H, 64, seed=12, device="cuda")
+    lst = harness.select(shape, agg.AGG_SELECT_HIGH, 0, k)
+    eager = harness.list_forward(shape, lst, q, k, v)
+    torch.cuda.synchronize()
+    buf = harness.list_forward(shape, lst, q, k, v, poison=True)
+    torch.cuda.synchronize()
+    M = lst.shape[1]
+
+    def run():
+        agg.agg_select_kv_indices(shape, agg.AGG_SELECT_HIGH, 0, k, lst)
+        agg.agg_kv_subsample_list(shape, lst, M, k, v, buf.Kc, buf.Vc, buf.kmean, buf.vmean,
+                                  buf.kept_bits, buf.n_dropped, buf.workspace, buf.workspace.numel())
+        agg.agg_global_attn_fwd_list(shape, M, q, k, v, buf.Kc, buf.Vc, buf.kmean, buf.vmean,
+                                     buf.kept_bits, buf.n_dropped, buf.O, buf.lse)
+
+    graph = _capture(run)
+    for replay in range(3):
+        buf.O.fill_(float("nan"))
+        buf.kept_bits.fill_(-1)
+        buf.n_dropped.fill_(-7)
+        buf.workspace.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf.O.view(torch.int16), eager.O.view(torch.int16)), replay
+        assert torch.equal(buf.lse, eager.lse) and torch.equal(buf.n_dropped, eager.n_dropped)
+        assert torch.equal(buf.kept_bits, eager.kept_bits) and torch.equal(buf.kmean, eager.kmean)
