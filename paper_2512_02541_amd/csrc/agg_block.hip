@@ -104,8 +104,8 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
 // row-major (one row per output channel), so both operands are contiguous along k.
 // One workgroup computes a 128 x 128 tile with 64-wide k steps, double-buffered in
 // LDS through registers; each of its four wavefronts owns 64 x 64.  LDS rows are 128
-// bytes with the 16-byte chunk index XOR-ed by (row & 7) so that both the row-wise
-// fills and the fragment reads spread over all banks.  The product is formed
+// bytes with the 16-byte chunk index XOR-ed by the row pair's number so that both the
+// row-wise fills and the fragment reads spread over all banks.  The product is formed
 // transposed (W rows as the MFMA A operand) so that a lane ends up with four
 // consecutive output channels of one token: 8-byte stores.
 // Requires K % 64 == 0 and N % 8 == 0.
@@ -119,7 +119,13 @@ constexpr int kGemmThreads = 256;
 constexpr int kTM = 128, kTN = 128, kTK = 64;
 constexpr int kGemmXcds = 8;
 
-__device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ (row & 7)); }
+// LDS has 64 banks of 4 bytes: a 16-byte access per lane is served 16 lanes at a time, which
+// must then fall on 16 different 16-byte slots of the 256-byte bank period.  Two 128-byte rows
+// share a period; XOR-ing the chunk with the row PAIR's number spreads 16 consecutive rows of
+// one chunk column (a fragment read) as well as the 16 chunks of a row pair (a fill).
+__device__ inline int swz(int row, int chunk) {
+  return (row >> 1) * 16 + ((((row & 1) << 3) | chunk) ^ ((row >> 1) & 7));
+}
 
 __global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
     const uint16_t* __restrict__ A, LinearOuts outs, const uint16_t* __restrict__ R, int64_t rows,

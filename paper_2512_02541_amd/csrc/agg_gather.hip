@@ -15,13 +15,24 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kSubThreads = 256;
 constexpr int kHeadGroup = 4;  // heads repacked per workgroup: 64 rows x 4 heads x 128 B = 32 KiB
 constexpr int kVPad = 72;      // padded row length (elements) of the raw V rows in LDS
+constexpr int kVHead = kTileRows * kVPad + 64;  // elements between two heads' V rows in LDS
 
 // LDS of the gather role
 struct GatherLds {
   uint16_t k[kHeadGroup][kTileElems];        // K in fragment order
-  uint16_t v[kHeadGroup][kTileRows][kVPad];  // raw V rows
+  // raw V rows, padded to kVPad; heads are a further 128 bytes apart so that the two heads a
+  // 16-lane LDS access covers start in different halves of the 256-byte bank period
+  uint16_t v[kHeadGroup * kVHead];
   int64_t tok[kTileRows];
 };
+
+// Where fragment-order slot `slot` of head hl waits in LDS.  The 16 lanes that the 64-bank LDS
+// serves together hold, on the fill side, the eight chunks of one row for two heads: their
+// slots differ only in bits 5..7 (and in the head), so those bits are folded into the low four;
+// the drain side reads 16 consecutive slots, which the fold permutes among themselves.
+__device__ inline int k_lds_pos(int slot, int hl) {
+  return slot ^ (((slot >> 5) & 7) | ((hl & 1) << 3));
+}
 
 // Gather role: one 64-row tile of the compacted set for kHeadGroup heads.  Reads are
 // 128-byte row segments (512 B contiguous per token for the four heads); writes are whole
@@ -69,8 +80,8 @@ __device__ inline void gather_tile(const Geom& g, const uint16_t* __restrict__ K
     }
     // K: chunk j covers channels 8j..8j+7 -> slot (((row/32)*4 + j/2)*2 + j%2)*32 + row%32
     int kslot = (((row >> 5) * 4 + (j >> 1)) * 2 + (j & 1)) * 32 + (row & 31);
-    *reinterpret_cast<u32x4*>(&s.k[hl][kslot * 8]) = kv;
-    *reinterpret_cast<u32x4*>(&s.v[hl][row][j * 8]) = vv;
+    *reinterpret_cast<u32x4*>(&s.k[hl][k_lds_pos(kslot, hl) * 8]) = kv;
+    *reinterpret_cast<u32x4*>(&s.v[hl * kVHead + row * kVPad + j * 8]) = vv;
   }
   __syncthreads();
 
@@ -81,7 +92,8 @@ __device__ inline void gather_tile(const Geom& g, const uint16_t* __restrict__ K
     int hl = c / (kTileElems / 8);
     int slot = c % (kTileElems / 8);
     int64_t base = (((int64_t)b * g.H + (h0 + hl)) * ntiles + tile) * kTileElems + slot * 8;
-    *reinterpret_cast<u32x4*>(Kc + base) = *reinterpret_cast<const u32x4*>(&s.k[hl][slot * 8]);
+    *reinterpret_cast<u32x4*>(Kc + base) =
+        *reinterpret_cast<const u32x4*>(&s.k[hl][k_lds_pos(slot, hl) * 8]);
     // V slot = (t*2 + gg)*64 + d holds rows 16t + 8*(e/4) + 4gg + e%4, e = 0..7, of channel d
     int d = slot & 63;
     int gg = (slot >> 6) & 1;
@@ -92,7 +104,8 @@ __device__ inline void gather_tile(const Geom& g, const uint16_t* __restrict__ K
       int ea = 2 * e2, eb = 2 * e2 + 1;
       int ra = 16 * t + 8 * (ea >> 2) + 4 * gg + (ea & 3);
       int rb = 16 * t + 8 * (eb >> 2) + 4 * gg + (eb & 3);
-      w[e2] = (uint32_t)s.v[hl][ra][d] | ((uint32_t)s.v[hl][rb][d] << 16);
+      w[e2] = (uint32_t)s.v[hl * kVHead + ra * kVPad + d] |
+              ((uint32_t)s.v[hl * kVHead + rb * kVPad + d] << 16);
     }
     u32x4 out = {w[0], w[1], w[2], w[3]};
     *reinterpret_cast<u32x4*>(Vc + base) = out;
