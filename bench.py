@@ -184,11 +184,10 @@ def run_only(args, log):
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        for _ in range(args.steps):
-            dst.copy_(src)
-        torch.cuda.synchronize()
+        ms, mn = time_events(lambda: dst.copy_(src), args.steps, 1)
         print(json.dumps({"only": "copy", "bytes_read": src.numel() * 4,
-                          "bytes_written": src.numel() * 4, "launches": args.steps}))
+                          "bytes_written": src.numel() * 4, "launches": args.steps + 1,
+                          "ms": ms, "gbs_read_plus_write": 2 * src.numel() * 4 / (ms * 1e-3) / 1e9}))
         return 0
     w = inputs.WORKLOADS[args.workload]
     shape = harness.shape_of(w)
