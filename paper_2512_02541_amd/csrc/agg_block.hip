@@ -102,8 +102,10 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
 // Linear layer  Y[m, n] = sum_k A[m, k] W[n, k] + bias[n] (+ R[m, n]),  bf16 in/out,
 // fp32 accumulation on v_mfma_f32_32x32x16_bf16.  A: [rows, K] row-major; W: [N, K]
 // row-major (one row per output channel), so both operands are contiguous along k.
-// One workgroup computes a 128 x 128 tile with 64-wide k steps, double-buffered in
-// LDS through registers; each of its four wavefronts owns 64 x 64.  LDS rows are 128
+// One workgroup (8 wavefronts) computes a 256 x 256 tile with 64-wide k steps,
+// double-buffered in LDS (128 KiB) through registers; each wavefront owns 64 tokens x 128
+// channels: six fragment reads feed eight MFMAs, and a tile's operands are fetched from L2
+// half as often as with 128 x 128 tiles.  LDS rows are 128
 // bytes with the 16-byte chunk index XOR-ed by the row pair's number so that both the
 // row-wise fills and the fragment reads spread over all banks.  The product is formed
 // transposed (W rows as the MFMA A operand) so that a lane ends up with four
@@ -115,9 +117,10 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
 // run on the same XCD, so a token tile is fetched from HBM once and then served by that
 // XCD's L2 to all of them.
 // ---------------------------------------------------------------------------
-constexpr int kGemmThreads = 256;
-constexpr int kTM = 128, kTN = 128, kTK = 64;
+constexpr int kGemmThreads = 512;
+constexpr int kTM = 256, kTN = 256, kTK = 64;
 constexpr int kGemmXcds = 8;
+constexpr int kStage = (kTM * 8) / kGemmThreads;  // 16-byte chunks per thread and operand (4)
 
 // LDS has 64 banks of 4 bytes: a 16-byte access per lane is served 16 lanes at a time, which
 // must then fall on 16 different 16-byte slots of the 256-byte bank period.  Two 128-byte rows
@@ -127,7 +130,7 @@ __device__ inline int swz(int row, int chunk) {
   return (row >> 1) * 16 + ((((row & 1) << 3) | chunk) ^ ((row >> 1) & 7));
 }
 
-__global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
+__global__ __launch_bounds__(kGemmThreads, 1) void linear_kernel(
     const uint16_t* __restrict__ A, LinearOuts outs, const uint16_t* __restrict__ R, int64_t rows,
     int N, int K, int gm, int gn) {
   __shared__ __align__(16) u32x4 sA[2][kTM * 8];
@@ -149,16 +152,16 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
   const int wave = tid >> 6;
   const int l32 = lane & 31;
   const int g2 = lane >> 5;
-  const int wm = (wave & 1) * 64;   // this wavefront's 64 token rows inside the tile
-  const int wn = (wave >> 1) * 64;  // and its 64 output channels
+  const int wm = (wave & 3) * 64;    // this wavefront's 64 token rows inside the tile
+  const int wn = (wave >> 2) * 128;  // and its 128 output channels
   const int64_t m0 = (int64_t)mt * kTM;
   const int n0 = (nt_all % gn) * kTN;
 
-  // staging: 128 rows x 8 chunks per operand = 1024 chunks, 4 per thread
-  u32x4 ra[4], rw[4];
+  // staging: 256 rows x 8 chunks per operand = 2048 chunks, 4 per thread
+  u32x4 ra[kStage], rw[kStage];
   auto gload = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < kStage; ++i) {
       const int c = tid + i * kGemmThreads;
       const int r = c >> 3, j = c & 7;
       int64_t am = m0 + r;
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
   };
   auto lstore = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < kStage; ++i) {
       const int c = tid + i * kGemmThreads;
       const int r = c >> 3, j = c & 7;
       sA[buf][swz(r, j)] = ra[i];
@@ -179,9 +182,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
     }
   };
 
-  f32x16 acc[2][2];  // [channel block][token block]
+  f32x16 acc[4][2];  // [channel block][token block]
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < 4; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -194,20 +197,27 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
     if (kt + 1 < nk) gload((kt + 1) * kTK);
+    // fragments of sub-step ks+1 are requested before the MFMAs of sub-step ks are issued, and
+    // the scheduler is kept from sinking those reads back down next to their use
+    Frag fw[2][4], fa[2][2];
+    auto load_frags = [&](int ks, int set) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) fw[set][a].u = sW[buf][swz(wn + a * 32 + l32, ks * 2 + g2)];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) fa[set][b].u = sA[buf][swz(wm + b * 32 + l32, ks * 2 + g2)];
+    };
+    load_frags(0, 0);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      Frag fw[2], fa[2];
+      if (ks < 3) load_frags(ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        fw[b].u = sW[buf][swz(wn + b * 32 + l32, ks * 2 + g2)];
-        fa[b].u = sA[buf][swz(wm + b * 32 + l32, ks * 2 + g2)];
-      }
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
-          acc[a][b] =
-              __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a].h, fa[b].h, acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][a].h, fa[ks & 1][b].h,
+                                                              acc[a][b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     if (kt + 1 < nk) lstore(buf ^ 1);
     __syncthreads();
@@ -219,7 +229,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_kernel(
     const int64_t m = m0 + wm + b * 32 + l32;
     if (m >= rows) continue;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const int n = n0 + wn + a * 32 + r4 * 8 + g2 * 4;
