@@ -370,7 +370,7 @@ def main():
                     help="comma list of further workloads timed (SGA only) into config.also")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=384)
+    ap.add_argument("--cpu-rows", type=int, default=1024)
     ap.add_argument("--sweep", action="store_true",
                     help="time the method's variants on --workload (sigma 2/4/6/9, both first-frame "
                          "rules, the four diag/mean flag combinations) and print one JSON line")

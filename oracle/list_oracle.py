@@ -14,6 +14,10 @@ Definitions used here (the readings are listed with the other readings of the pa
   * the random choice is a counter-based hash of (seed, batch, frame, window), written out
     in ``random_cell`` below, taken modulo the number of cells of the (clipped) window.
 
+The paper prints no number that depends on the definition of "feature magnitude", on the
+random generator or on how an arbitrary list treats unlisted special tokens: parity unpinned
+for those three choices (the attention over a given list is pinned as below).
+
 Pins (tests/test_oracle_pins.py): the FIRST rule reproduces the grid rule's index list and
 the C oracle's outputs; a list of all tokens gives dense attention; list order does not
 matter; brute-force masked dense attention on random lists; window membership, one pick per
