@@ -12,6 +12,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -120,6 +121,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
 constexpr int kGemmThreads = 512;
 constexpr int kTM = 256, kTN = 256, kTK = 64;
 constexpr int kGemmXcds = 8;
+constexpr int kEpiStride = 64 + 4;  // floats per token row of the epilogue's LDS tile (padded)
 constexpr int kStage = (kTM * 8) / kGemmThreads;  // 16-byte chunks per thread and operand (4)
 
 // LDS has 64 banks of 4 bytes: a 16-byte access per lane is served 16 lanes at a time, which
@@ -130,6 +132,7 @@ __device__ inline int swz(int row, int chunk) {
   return (row >> 1) * 16 + ((((row & 1) << 3) | chunk) ^ ((row >> 1) & 7));
 }
 
+template <bool kResidual>
 __global__ __launch_bounds__(kGemmThreads, 1) void linear_kernel(
     const uint16_t* __restrict__ A, LinearOuts outs, const uint16_t* __restrict__ R, int64_t rows,
     int N, int K, int gm, int gn) {
@@ -223,31 +226,58 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_kernel(
     __syncthreads();
   }
 
-  // acc[a][b][r]: channel n0 + wn + 32a + 8(r/4) + 4g2 + r%4, token m0 + wm + 32b + l32
+  // Epilogue.  acc[a][b][r] is channel n0 + wn + 32a + 8(r/4) + 4g2 + r%4 of token
+  // m0 + wm + 32b + l32: written straight from there a lane would store 8 bytes per 2 KiB-apart
+  // row.  Instead each wavefront turns its tile through a private piece of the (now idle) LDS,
+  // 32 tokens x 64 channels of float at a time, and writes whole 128-byte runs of a token row:
+  // 16 lanes x 4 channels.  Bias and residual are added in float before the one rounding.
+  float* epi = reinterpret_cast<float*>(wave < 4 ? &sA[0][0] : &sW[0][0]) + (wave & 3) * (32 * kEpiStride);
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    const int64_t m = m0 + wm + b * 32 + l32;
-    if (m >= rows) continue;
+  for (int b = 0; b < 2; ++b)
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int half = 0; half < 2; ++half) {
+      const int ch = (lane & 15) * 4;                  // channel inside this 64-channel run
+      const int n = n0 + wn + half * 64 + ch;
+      // residual values of the eight rows this lane will finish, requested before the LDS turn
+      u32x2 rr[8];
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int n = n0 + wn + a * 32 + r4 * 8 + g2 * 4;
-        if (n >= N) continue;
-        float o[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = acc[a][b][r4 * 4 + i] + (bias ? bias[n + i] : 0.f);
-        if (R) {
-          u32x2 rr = *reinterpret_cast<const u32x2*>(R + m * N + n);
-          o[0] += lo16(rr[0]);
-          o[1] += hi16(rr[0]);
-          o[2] += lo16(rr[1]);
-          o[3] += hi16(rr[1]);
-        }
-        u32x2 w = {pack2(o[0], o[1]), pack2(o[2], o[3])};
-        *reinterpret_cast<u32x2*>(Y + m * N + n) = w;
+      for (int i = 0; i < 8; ++i) {
+        const int64_t m = m0 + wm + b * 32 + i * 4 + (lane >> 4);
+        rr[i] = u32x2{0u, 0u};
+        if (kResidual && m < rows && n < N) rr[i] = *reinterpret_cast<const u32x2*>(R + m * N + n);
       }
-  }
+#pragma unroll
+      for (int a2 = 0; a2 < 2; ++a2)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int a = half * 2 + a2;
+          f32x4 v4 = {acc[a][b][r4 * 4 + 0], acc[a][b][r4 * 4 + 1], acc[a][b][r4 * 4 + 2],
+                      acc[a][b][r4 * 4 + 3]};
+          *reinterpret_cast<f32x4*>(epi + l32 * kEpiStride + a2 * 32 + r4 * 8 + g2 * 4) = v4;
+        }
+      f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+      if (bias && n < N) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bv[i] = bias[n + i];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int t = i * 4 + (lane >> 4);             // token inside this 32-token block
+        const int64_t m = m0 + wm + b * 32 + t;
+        f32x4 o = *reinterpret_cast<const f32x4*>(epi + t * kEpiStride + ch);
+        if (m < rows && n < N) {
+          o += bv;
+          if (kResidual) {
+            o[0] += lo16(rr[i][0]);
+            o[1] += hi16(rr[i][0]);
+            o[2] += lo16(rr[i][1]);
+            o[3] += hi16(rr[i][1]);
+          }
+          u32x2 w = {pack2(o[0], o[1]), pack2(o[2], o[3])};
+          *reinterpret_cast<u32x2*>(Y + m * N + n) = w;
+        }
+      }
+    }
 }
 
 hipError_t launch_layernorm(const void* x, const float* gamma, const float* beta, void* y,
@@ -269,8 +299,12 @@ hipError_t launch_linear(const void* A, const LinearOuts& outs, const void* R, i
   const int64_t groups = (gm + kGemmXcds - 1) / kGemmXcds * kGemmXcds * gn * outs.count;
   if (groups > 0x7FFFFFFF) return hipErrorInvalidConfiguration;
   (void)hipGetLastError();
-  hipLaunchKernelGGL(linear_kernel, dim3((unsigned)groups), dim3(kGemmThreads), 0, st,
-                     (const uint16_t*)A, outs, (const uint16_t*)R, rows, N, K, (int)gm, gn);
+  if (R)
+    hipLaunchKernelGGL(linear_kernel<true>, dim3((unsigned)groups), dim3(kGemmThreads), 0, st,
+                       (const uint16_t*)A, outs, (const uint16_t*)R, rows, N, K, (int)gm, gn);
+  else
+    hipLaunchKernelGGL(linear_kernel<false>, dim3((unsigned)groups), dim3(kGemmThreads), 0, st,
+                       (const uint16_t*)A, outs, (const uint16_t*)R, rows, N, K, (int)gm, gn);
   return hipGetLastError();
 }
 
