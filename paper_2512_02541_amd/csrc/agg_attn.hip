@@ -54,6 +54,7 @@ constexpr int kAttnThreads = 256;
 constexpr int kQTile = 256;  // queries per workgroup
 constexpr int kXcds = 8;
 constexpr int kLdsTiles = 3;
+constexpr int kEpiStride = kHeadDim + 8;  // bf16 per query row of the epilogue's LDS tile (padded)
 constexpr int kChunks = kTileElems / 8;  // 16-byte chunks per K or V tile (512)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -91,7 +92,8 @@ __device__ inline void dma16(const u32x4* gsrc, uint32_t lds_wave_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(gsrc), "s"(lds_wave_base)
-               : "memory", "m0");
+               : "memory");  // M0 is a reserved register the compiler sets right before each of
+                             // its own uses (none in this kernel), so it is not listed
 }
 __device__ inline void tile_to_lds(const u32x4* __restrict__ src, u32x4* dst, int tid, int wave) {
   const uint32_t base = __builtin_amdgcn_readfirstlane(
@@ -454,26 +456,37 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sga_attn_kernel(
   }
 
   // ---- normalise and store ----
+  // A lane holds four consecutive channels of one query per register group: stored from there,
+  // every instruction would scatter 8-byte pieces over 64 rows that lie 2*H*64 bytes apart.
+  // Each wavefront instead turns its 64 x 64 tile through a private piece of the (now idle) K/V
+  // LDS and writes whole 128-byte (query, head) rows, eight per instruction.
+  __syncthreads();  // every wavefront is done with the K/V tiles
+  uint16_t* epi = (wave < 2 ? &sK[0][0] : &sV[0][0]) + (wave & 1) * (64 * kEpiStride);
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb) {
     const float l = l_fin[qb];
     const float inv = 1.0f / l;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int d0 = 32 * db + 8 * r4 + 4 * g2;
+        u32x2 w;
+        w[0] = pack_bf16(Oacc[qb][db][r4 * 4 + 0] * inv, Oacc[qb][db][r4 * 4 + 1] * inv);
+        w[1] = pack_bf16(Oacc[qb][db][r4 * 4 + 2] * inv, Oacc[qb][db][r4 * 4 + 3] * inv);
+        *reinterpret_cast<u32x2*>(epi + (qb * 32 + l32) * kEpiStride + d0) = w;
+      }
     const int64_t q = (int64_t)qt * kQTile + wave * 64 + qb * 32 + l32;
-    if (q < g.NQ) {
-      const int64_t qbase = (((int64_t)b * g.NQ + q) * g.H + h) * kHeadDim;
+    if (lse && g2 == 0 && q < g.NQ)
+      lse[((int64_t)b * g.H + h) * g.NQ + q] = (m_fin[qb] + log2f(l)) * kLn2;
+  }
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int d0 = 32 * db + 8 * r4 + 4 * g2;
-          u32x2 w;
-          w[0] = pack_bf16(Oacc[qb][db][r4 * 4 + 0] * inv, Oacc[qb][db][r4 * 4 + 1] * inv);
-          w[1] = pack_bf16(Oacc[qb][db][r4 * 4 + 2] * inv, Oacc[qb][db][r4 * 4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(O + qbase + d0) = w;
-        }
-      if (lse && g2 == 0)
-        lse[((int64_t)b * g.H + h) * g.NQ + q] = (m_fin[qb] + log2f(l)) * kLn2;
-    }
+  for (int i = 0; i < 8; ++i) {
+    const int row = i * 8 + (lane >> 3);
+    const int64_t q = (int64_t)qt * kQTile + wave * 64 + row;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(epi + row * kEpiStride + (lane & 7) * 8);
+    if (q < g.NQ)
+      *reinterpret_cast<u32x4*>(O + (((int64_t)b * g.NQ + q) * g.H + h) * kHeadDim + (lane & 7) * 8) = v;
   }
 }
 
