@@ -274,6 +274,13 @@ def run_sweep(args, log):
             name, ms_sel, ms_sub, ms_att))
         del lb, lst
         torch.cuda.empty_cache()
+    # cell-mean variant: pooled compacted set, attention without extras
+    pb = harness.pool_forward(shape, q, k, v)
+    ms_pool, _ = time_events(lambda: agg.agg_kv_pool(pb.shape, k, v, pb.Kc, pb.Vc), args.steps, 1)
+    ms_patt, _ = time_events(lambda: harness.attend(pb, q, k, v), args.steps, 1)
+    list_rows.append({"rule": "cell_mean", "M": M, "ms_select": 0.0, "ms_subsample_list": ms_pool,
+                      "ms_attn_list": ms_patt})
+    log("rule cell_mean: pooling %.3f ms, attn %.2f ms" % (ms_pool, ms_patt))
     print(json.dumps({"sweep": args.workload, "NQ": w.NQ, "rows": rows, "selection_rules": list_rows}))
     return 0
 

@@ -220,6 +220,16 @@ enum {
 int agg_select_kv_indices(const agg_shape* shape, int rule, uint64_t seed, const void* K,
                           int32_t* list, void* hip_stream);
 
+/*
+ * The cell-mean variant of the same ablation: Kc/Vc (agg_kv_compact_bytes each, M rows as for
+ * agg_kv_subsample) where the row of a window is the MEAN of the window's tokens (float32
+ * accumulation, rounded to bf16 once) instead of its first token; special tokens and a
+ * whole-kept frame 0 are copied.  The paper runs this variant without the self term and without
+ * the mean component: call agg_global_attn_fwd on the result with flags = 0.
+ */
+int agg_kv_pool(const agg_shape* shape, const void* K, const void* V, void* Kc, void* Vc,
+                void* hip_stream);
+
 /* Host only.  Size of ONE compacted tensor for a list of M_list rows, and its M_pad. */
 int agg_list_compact_bytes(const agg_shape* shape, int64_t M_list, size_t* bytes, int64_t* M_pad);
 

@@ -161,3 +161,55 @@ def attn_rows(shape, kv_list: np.ndarray, q_bits, k_bits, v_bits, rows):
                 O[b, r, h] = (e / den) @ vals
                 lse[b, h, r] = mx + np.log(den)
     return O, lse, km, vm, nd
+
+
+def pool(shape, k_bits, v_bits):
+    """Cell-mean variant of the same ablation: float64 [B, H, M, D] key and value rows where a
+    window's row is the mean over the window's tokens; special tokens and a whole-kept frame 0
+    are copied.  Rows are in the order of the grid rule's ascending list."""
+    P, T = shape.n_special, shape.n_h * shape.n_w
+    L = P + T
+    NQ = shape.N * L
+    k = _widen(k_bits).reshape(shape.B, NQ, shape.H, shape.D)
+    v = _widen(v_bits).reshape(shape.B, NQ, shape.H, shape.D)
+    groups = []                       # token ids averaged into each row
+    for f in range(shape.N):
+        base = f * L
+        groups.extend([[base + p] for p in range(P)])
+        if f == 0 and shape.keep_first_frame:
+            groups.extend([[base + P + t] for t in range(T)])
+            continue
+        for (r0, c0, nr, nc) in windows(shape):
+            groups.append([base + P + (r0 + i) * shape.n_w + (c0 + j)
+                           for i in range(nr) for j in range(nc)])
+    kp = np.stack([k[:, g].mean(axis=1) for g in groups], axis=2)   # [B, H, M, D]
+    vp = np.stack([v[:, g].mean(axis=1) for g in groups], axis=2)
+    return kp, vp, groups
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """float64 -> nearest bf16 value (ties to even), returned as float64."""
+    f = x.astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def attn_over_rows(shape, q_bits, kp, vp, rows):
+    """Plain softmax attention of the listed queries over given key/value rows [B, H, M, D]."""
+    L = shape.n_special + shape.n_h * shape.n_w
+    NQ = shape.N * L
+    q = _widen(q_bits).reshape(shape.B, NQ, shape.H, shape.D)
+    rows = np.asarray(rows, dtype=np.int64)
+    scale = float(np.float32(shape.scale))
+    O = np.zeros((shape.B, len(rows), shape.H, shape.D))
+    lse = np.zeros((shape.B, shape.H, len(rows)))
+    for b in range(shape.B):
+        for h in range(shape.H):
+            z = scale * (q[b, rows, h] @ kp[b, h].T)          # [nrows, M]
+            mx = z.max(axis=1, keepdims=True)
+            e = np.exp(z - mx)
+            den = e.sum(axis=1, keepdims=True)
+            O[b, :, h] = (e / den) @ vp[b, h]
+            lse[b, h] = (mx + np.log(den))[:, 0]
+    return O, lse

@@ -63,7 +63,7 @@ EXPORTS = [
     "agg_dense_global_attn_fwd", "agg_frame_workspace_bytes", "agg_frame_attn_fwd",
     "agg_block_workspace_bytes", "agg_global_block_fwd",
     "agg_select_kv_indices", "agg_list_compact_bytes", "agg_list_workspace_bytes",
-    "agg_kv_subsample_list", "agg_global_attn_fwd_list",
+    "agg_kv_subsample_list", "agg_global_attn_fwd_list", "agg_kv_pool",
 ]
 
 AGG_SELECT_FIRST = 0
@@ -144,6 +144,7 @@ def lib():
                                         ctypes.c_size_t, vp]
     L.agg_global_attn_fwd_list.argtypes = [shp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                            vp, vp, vp]
+    L.agg_kv_pool.argtypes = [shp, vp, vp, vp, vp, vp]
     _lib = L
     return L
 
@@ -302,3 +303,8 @@ def agg_global_attn_fwd_list(shape, M_list, Q, K, V, Kc, Vc, kmean, vmean, kept_
                                           _ptr(V), _ptr(Kc), _ptr(Vc), _ptr(kmean), _ptr(vmean),
                                           _ptr(kept_bits), _ptr(n_dropped), _ptr(O), _ptr(lse),
                                           _stream(stream)), "agg_global_attn_fwd_list")
+
+
+def agg_kv_pool(shape, K, V, Kc, Vc, stream=None):
+    _check(lib().agg_kv_pool(ctypes.byref(shape), _ptr(K), _ptr(V), _ptr(Kc), _ptr(Vc),
+                             _stream(stream)), "agg_kv_pool")

@@ -260,6 +260,17 @@ int agg_select_kv_indices(const agg_shape* shape, int rule, uint64_t seed, const
   return AGG_OK;
 }
 
+int agg_kv_pool(const agg_shape* shape, const void* K, const void* V, void* Kc, void* Vc,
+                void* hip_stream) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (!K || !V || !Kc || !Vc) return AGG_ERR_NULL;
+  if (misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc)) return AGG_ERR_ALIGN;
+  if (launch_pool(g, K, V, Kc, Vc, (hipStream_t)hip_stream) != hipSuccess) return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
 int agg_list_compact_bytes(const agg_shape* shape, int64_t M_list, size_t* bytes, int64_t* M_pad) {
   Geom g;
   int rc = list_geom(shape, M_list, &g);

@@ -24,6 +24,7 @@ struct GatherLds {
   // 16-lane LDS access covers start in different halves of the 256-byte bank period
   uint16_t v[kHeadGroup * kVHead];
   int64_t tok[kTileRows];
+  int32_t win[kTileRows];  // pooled variant: window rows << 8 | window columns of the row's cell
 };
 
 // Where fragment-order slot `slot` of head hl waits in LDS.  The 16 lanes that the 64-bank LDS
@@ -39,6 +40,37 @@ __device__ inline int k_lds_pos(int slot, int hl) {
 // 8 KiB tiles, fully coalesced.  K chunks are routed through LDS to their fragment-order
 // slot; V is transposed through LDS (the PV MFMA wants eight keys of one channel in one
 // 16-byte operand).
+// Mean of `cells` 16-byte chunks of bf16 (a window's tokens at the same head and channels), in
+// float, rounded to bf16 once.
+__device__ inline u32x4 window_mean(const uint16_t* __restrict__ T, int64_t off0, int64_t row_stride,
+                                    int64_t cell_stride, int wrows, int wcols) {
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int r = 0; r < wrows; ++r)
+    for (int c = 0; c < wcols; ++c) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(T + off0 + r * row_stride + c * cell_stride);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += __uint_as_float(v[i] << 16);
+        acc[2 * i + 1] += __uint_as_float(v[i] & 0xFFFF0000u);
+      }
+    }
+  const float inv = 1.0f / (float)(wrows * wcols);
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  u32x4 out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f32x2 pr = {acc[2 * i] * inv, acc[2 * i + 1] * inv};
+    out[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+  }
+  return out;
+}
+
+// kPool: a kept patch of a subsampled frame stands for its whole window and the row written is
+// the window's mean (the cell-mean variant of the supplementary ablation) instead of a copy.
+template <bool kPool = false>
 __device__ inline void gather_tile(const Geom& g, const uint16_t* __restrict__ K,
                                    const uint16_t* __restrict__ V, uint16_t* __restrict__ Kc,
                                    uint16_t* __restrict__ Vc, int32_t* __restrict__ idx,
@@ -61,6 +93,18 @@ __device__ inline void gather_tile(const Geom& g, const uint16_t* __restrict__ K
       }
     }
     s.tok[tid] = tok;
+    if (kPool) {
+      int32_t win = (1 << 8) | 1;
+      if (tok >= 0) {
+        const int64_t frame = tok / g.L;
+        const int32_t slot = (int32_t)(tok % g.L);
+        if (slot >= g.P && !(frame == 0 && g.keep_first)) {
+          const int32_t r = (slot - g.P) / g.n_w, c = (slot - g.P) % g.n_w;
+          win = (min(g.s_h, g.n_h - r) << 8) | min(g.s_w, g.n_w - c);
+        }
+      }
+      s.win[tid] = win;
+    }
     if (idx && b == 0 && hgrp == 0 && m < g.M) idx[m] = (int32_t)tok;
   }
   __syncthreads();
@@ -75,8 +119,15 @@ __device__ inline void gather_tile(const Geom& g, const uint16_t* __restrict__ K
     u32x4 kv = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
     if (tok >= 0) {
       int64_t off = (((int64_t)b * g.NQ + tok) * g.H + (h0 + hl)) * kHeadDim + j * 8;
-      kv = *reinterpret_cast<const u32x4*>(K + off);
-      vv = *reinterpret_cast<const u32x4*>(V + off);
+      if (kPool && s.win[row] != ((1 << 8) | 1)) {
+        const int wrows = s.win[row] >> 8, wcols = s.win[row] & 255;
+        const int64_t cell = (int64_t)g.H * kHeadDim;  // elements between neighbouring tokens
+        kv = window_mean(K, off, cell * g.n_w, cell, wrows, wcols);
+        vv = window_mean(V, off, cell * g.n_w, cell, wrows, wcols);
+      } else {
+        kv = *reinterpret_cast<const u32x4*>(K + off);
+        vv = *reinterpret_cast<const u32x4*>(V + off);
+      }
     }
     // K: chunk j covers channels 8j..8j+7 -> slot (((row/32)*4 + j/2)*2 + j%2)*32 + row%32
     int kslot = (((row >> 5) * 4 + (j >> 1)) * 2 + (j & 1)) * 32 + (row & 31);
@@ -397,6 +448,31 @@ hipError_t launch_subsample(const Geom& g, const void* K, const void* V, void* K
   hipLaunchKernelGGL(mean_final_kernel, grid2, dim3(kFinalCols * kFinalGroups), 0, st, g,
                      (const float*)workspace, plan.nchunks, kmean, vmean, (const int32_t*)nullptr,
                      (int32_t*)nullptr);
+  return hipGetLastError();
+}
+
+// Cell-mean variant: the compacted set holds, per window, the mean of its tokens.
+__global__ __launch_bounds__(kSubThreads) void pool_kernel(Geom g, const uint16_t* __restrict__ K,
+                                                           const uint16_t* __restrict__ V,
+                                                           uint16_t* __restrict__ Kc,
+                                                           uint16_t* __restrict__ Vc, int n_gather,
+                                                           int nhg) {
+  __shared__ __align__(16) GatherLds lds;
+  const int b = blockIdx.x / n_gather;
+  const int rr = blockIdx.x % n_gather;
+  gather_tile<true>(g, K, V, Kc, Vc, nullptr, nullptr, rr / nhg, rr % nhg, b, lds);
+}
+
+hipError_t launch_pool(const Geom& g, const void* K, const void* V, void* Kc, void* Vc,
+                       hipStream_t st) {
+  const int nhg = (g.H + kHeadGroup - 1) / kHeadGroup;
+  const int64_t n_gather = (g.M_pad / kTileRows) * nhg;
+  const int64_t groups = n_gather * g.B;
+  if (groups > 0x7FFFFFFF || n_gather > 0x3FFFFFFF) return hipErrorInvalidConfiguration;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(pool_kernel, dim3((unsigned)groups), dim3(kSubThreads), 0, st, g,
+                     (const uint16_t*)K, (const uint16_t*)V, (uint16_t*)Kc, (uint16_t*)Vc,
+                     (int)n_gather, nhg);
   return hipGetLastError();
 }
 

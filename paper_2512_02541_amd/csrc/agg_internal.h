@@ -131,6 +131,9 @@ hipError_t launch_subsample_list(const Geom& g, const int32_t* list, const void*
                                  int32_t* nd_out, void* workspace, hipStream_t st);
 hipError_t launch_select(const Geom& g, int rule, uint64_t seed, const void* K, int32_t* list,
                          hipStream_t st);
+// compacted set whose rows are window means (cell-mean variant)
+hipError_t launch_pool(const Geom& g, const void* K, const void* V, void* Kc, void* Vc,
+                       hipStream_t st);
 
 hipError_t launch_layernorm(const void* x, const float* gamma, const float* beta, void* y,
                             int64_t rows, int C, float eps, hipStream_t st);

@@ -176,3 +176,15 @@ def select(shape, rule, seed, K):
     out = torch.full((shape.B, M), -1, dtype=torch.int32, device=K.device)
     agg.agg_select_kv_indices(shape, rule, seed, K, out)
     return out
+
+
+def pool_forward(shape, Q, K, V):
+    """Cell-mean variant: pooled compacted set, then attention without extras (flags 0)."""
+    plain = agg.make_shape(shape.B, shape.N, shape.n_h, shape.n_w, shape.n_special, shape.H,
+                           shape.D, shape.s_h, shape.s_w, shape.keep_first_frame, 0, shape.scale, 0.0)
+    buf = alloc(plain, Q.device, poison=True)
+    buf.kmean.zero_()
+    buf.vmean.zero_()
+    agg.agg_kv_pool(plain, K, V, buf.Kc, buf.Vc)
+    attend(buf, Q, K, V)
+    return buf

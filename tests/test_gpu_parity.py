@@ -566,3 +566,35 @@ def test_hip_graph_replays_of_block_and_list_paths():
         assert torch.equal(buf.O.view(torch.int16), eager.O.view(torch.int16)), replay
         assert torch.equal(buf.lse, eager.lse) and torch.equal(buf.n_dropped, eager.n_dropped)
         assert torch.equal(buf.kept_bits, eager.kept_bits) and torch.equal(buf.kmean, eager.kmean)
+
+
+@pytest.mark.parametrize("case", [(2, 3, 7, 8, 5, 4, 3, 3, 1), (1, 2, 16, 16, 5, 16, 2, 2, 0),
+                                  (1, 3, 5, 7, 2, 3, 1, 2, 1)])
+def test_cell_mean_pooling(case):
+    """agg_kv_pool: rows are window means (one bf16 rounding), and attention over them without
+    extras matches plain attention over the oracle's pooled rows."""
+    from oracle import list_oracle as lo
+
+    B, N, n_h, n_w, P, H, s_h, s_w, kf = case
+    shape = agg.make_shape(B, N, n_h, n_w, P, H, 64, s_h, s_w, kf)
+    q, k, v = inputs.iid_qkv(B, shape.NQ, H, 64, seed=740 + n_h, device="cuda")
+    buf = harness.pool_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    kp, vp, groups = lo.pool(lshape(shape), kb, vb)
+    M = len(groups)
+    assert M == buf.M
+    got_k = harness.decode_compact(buf.Kc, B, H, M, buf.M_pad, "k").double().cpu().numpy()
+    got_v = harness.decode_compact(buf.Vc, B, H, M, buf.M_pad, "v").double().cpu().numpy()
+    assert (got_k[:, :, M:] == 0).all() and (got_v[:, :, M:] == 0).all()
+    # float32 mean rounded once against float64 mean rounded once: at most one bf16 step apart
+    for got, want in ((got_k[:, :, :M], kp), (got_v[:, :, :M], vp)):
+        assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-30).all()
+        exact = got == lo.round_to_bf16(want)
+        assert exact.mean() > 0.999
+    single = np.array([len(g) == 1 for g in groups])
+    assert np.array_equal(got_k[:, :, :M][:, :, single], kp[:, :, single])   # copies are exact
+    rows = np.arange(shape.NQ, dtype=np.int64)
+    want_o, want_lse = lo.attn_over_rows(lshape(shape), qb, lo.round_to_bf16(kp),
+                                         lo.round_to_bf16(vp), rows)
+    check_output(buf.O, buf.lse, want_o, want_lse, rows, "cell mean")

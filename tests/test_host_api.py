@@ -185,6 +185,10 @@ def test_error_paths_before_any_launch():
               lws, None) == -1
     assert sl(ctypes.byref(good), fake, 0, fake, fake, fake, fake, fake, fake, fake, fake, fake,
               lws, None) == -2
+    pool = lib.agg_kv_pool
+    assert pool(ctypes.byref(good), fake, fake, fake, None, None) == -1
+    assert pool(ctypes.byref(good), fake, odd, fake, fake, None) == -4
+    assert pool(ctypes.byref(bad), fake, fake, fake, fake, None) == -3
     al = lib.agg_global_attn_fwd_list
     assert al(ctypes.byref(good), 65, fake, fake, fake, fake, fake, fake, fake, None, fake, fake,
               None, None) == -1

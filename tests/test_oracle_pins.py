@@ -692,3 +692,54 @@ def test_random_rule_is_uniform_over_cells_and_depends_on_seed():
     c = [lo.random_cell(1 + (1 << 32), 0, 1, w, 8, 9) for w in range(64)]
     assert a != b and a != c
     assert all(0 <= x < 9 for x in a)
+
+
+def test_cell_mean_pooling_oracle():
+    from oracle import list_oracle as lo
+
+    shape = _list_shape(B=2, N=3, n_h=5, n_w=7, s_h=2, s_w=3, keep_first_frame=1)
+    q, k, v = draw(shape, seed=66)
+    kp, vp, groups = lo.pool(shape, bits(k), bits(v))
+    grid = orc.kept_indices(shape)
+    assert kp.shape == (shape.B, shape.H, len(grid), shape.D)
+    assert [g[0] for g in groups] == grid.tolist()           # a row stands where its first token stood
+    kd = k.double().numpy()
+    L, P = shape.L, shape.n_special
+    for m, g0 in enumerate(grid):                             # explicit loop over each window
+        if g0 % L < P or g0 // L == 0:
+            assert np.array_equal(kp[:, :, m], kd[:, g0])
+            continue
+        r0, c0 = divmod(g0 % L - P, shape.n_w)
+        acc = np.zeros_like(kd[:, 0])
+        n = 0
+        for r in range(r0, min(r0 + shape.s_h, shape.n_h)):
+            for c in range(c0, min(c0 + shape.s_w, shape.n_w)):
+                acc += kd[:, g0 // L * L + P + r * shape.n_w + c]
+                n += 1
+        assert n == len(groups[m]) and np.abs(kp[:, :, m] - acc / n).max() < 1e-14
+    # every patch of a subsampled frame is averaged exactly once
+    seen = sorted(t for g in groups for t in g)
+    assert seen == list(range(shape.NQ))
+    # strides (1,1): nothing is pooled, attention over the rows is dense attention
+    one = _list_shape(B=1, s_h=1, s_w=1)
+    q1, k1, v1 = draw(one, seed=67)
+    kp1, vp1, _ = lo.pool(one, bits(k1), bits(v1))
+    assert np.array_equal(kp1, k1.double().numpy().transpose(0, 2, 1, 3))
+    rows = np.arange(one.NQ)
+    O, lse = lo.attn_over_rows(one, bits(q1), kp1, vp1, rows)
+    want, want_lse = orc.dense_rows(one, bits(q1), bits(k1), bits(v1), rows)
+    assert np.abs(O - want).max() < 1e-11 and np.abs(lse - want_lse).max() < 1e-11
+    # K and V constant inside every window: the mean is the first token, and the result is the
+    # subsample-only variant of the grid rule
+    kc, vc = k.clone(), v.clone()
+    for g in groups:
+        kc[:, g] = k[:, g[0]:g[0] + 1]
+        vc[:, g] = v[:, g[0]:g[0] + 1]
+    kp2, vp2, _ = lo.pool(shape, bits(kc), bits(vc))
+    O2, _ = lo.attn_over_rows(shape, bits(q), kp2, vp2, np.arange(shape.NQ))
+    plain = orc.Shape(**{**shape.__dict__, "flags": 0})
+    assert np.abs(O2 - orc.sga(plain, bits(q), bits(kc), bits(vc))["O"]).max() < 1e-11
+    # rounding helper: exact on representable values, nearest-even otherwise
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -0.3])
+    r = lo.round_to_bf16(x)
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.0 + 2.0 ** -6 and abs(r[3] + 0.3) < 2.0 ** -9 * 0.3 * 2
