@@ -1,9 +1,8 @@
 // The parts of a global-attention block around the attention itself (AVGGT Sec. 4.2: a
 // block is converted or subsampled with all its other components unchanged):
 // LayerNorm, the Q/K/V projections, the output projection with bias and residual.
-// They are a few percent of a block's time next to attention over 10^5..10^6 tokens, so
-// they are written for clarity on the same MFMA conventions as the attention kernel
-// rather than tuned to the last percent.
+// They are a few percent of a block's time next to attention over 10^5..10^6 tokens and
+// follow the MFMA conventions of the attention kernel.
 #include "agg_internal.h"
 
 namespace agg {
@@ -109,8 +108,9 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
 // half as often as with 128 x 128 tiles.  LDS rows are 128
 // bytes with the 16-byte chunk index XOR-ed by the row pair's number so that both the
 // row-wise fills and the fragment reads spread over all banks.  The product is formed
-// transposed (W rows as the MFMA A operand) so that a lane ends up with four
-// consecutive output channels of one token: 8-byte stores.
+// transposed (W rows as the MFMA A operand): a lane ends up with four consecutive output
+// channels of one token, and the epilogue turns the tile through LDS so that rows leave in
+// 128-byte runs.
 // Requires K % 64 == 0 and N % 8 == 0.
 //
 // One launch serves up to three weight matrices applied to the same input (the Q, K and V
