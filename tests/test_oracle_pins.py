@@ -743,3 +743,31 @@ def test_cell_mean_pooling_oracle():
     x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -0.3])
     r = lo.round_to_bf16(x)
     assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.0 + 2.0 ** -6 and abs(r[3] + 0.3) < 2.0 ** -9 * 0.3 * 2
+
+
+def test_shift_of_keys_orthogonal_to_the_query_changes_nothing():
+    """Adding to EVERY key a vector orthogonal to q_i shifts none of row i's logits (kept columns,
+    self column, mean column alike), so o_i is unchanged; values are dyadic so that the shifted
+    keys are exact in bf16."""
+    shape = small_shape(H=1, flags=orc.DIAG | orc.MEAN, mean_logit_bias=0.5)
+    rng = np.random.default_rng(17)
+    NQ, D = shape.NQ, shape.D
+    k = torch.tensor(rng.integers(-16, 17, size=(1, NQ, 1, D)) / 8.0, dtype=torch.float32)
+    v = torch.tensor(rng.integers(-16, 17, size=(1, NQ, 1, D)) / 8.0, dtype=torch.float32)
+    q = torch.tensor(rng.integers(-8, 9, size=(1, NQ, 1, D)) / 8.0, dtype=torch.float32)
+    u = torch.zeros(D)
+    rows = [3, 20, shape.L + shape.n_special + 1, NQ - 1]     # special, frame-0, dropped, last
+    for i in rows:
+        q[0, i, 0] = torch.tensor([1.0, 1.0, 0.5, -0.5] + [0.0] * (D - 4))
+    u[:4] = torch.tensor([1.0, -1.0, 1.0, 1.0])               # q_i . u = 1 - 1 + 0.5 - 0.5 = 0
+    k2 = k + u.view(1, 1, 1, D)
+    qb, vb = bits(q.to(torch.bfloat16)), bits(v.to(torch.bfloat16))
+    assert torch.equal(k2.to(torch.bfloat16).float(), k2)     # still exact
+    a = orc.sga(shape, qb, bits(k.to(torch.bfloat16)), vb, rows=np.array(rows))
+    b = orc.sga(shape, qb, bits(k2.to(torch.bfloat16)), vb, rows=np.array(rows))
+    assert np.abs(a["O"] - b["O"]).max() < 1e-13
+    assert np.abs(a["lse"] - b["lse"]).max() < 1e-13
+    # a shift that is NOT orthogonal does change the dropped query's row (the pin has teeth)
+    k3 = k + torch.tensor([1.0] + [0.0] * (D - 1)).view(1, 1, 1, D) * (torch.arange(NQ) % 2).view(1, NQ, 1, 1)
+    c = orc.sga(shape, qb, bits(k3.to(torch.bfloat16)), vb, rows=np.array(rows))
+    assert np.abs(a["O"] - c["O"]).max() > 1e-3
