@@ -306,8 +306,10 @@ def run_block(args, log):
     cws = [agg.make_block_weights(l["ln_gamma"], l["ln_beta"], l["ln_eps"], l["w_q"], l["w_k"],
                                   l["w_v"], l["w_o"], l["b_q"], l["b_k"], l["b_v"], l["b_o"])
            for l in layers]
-    modes = [agg.AGG_BLOCK_FRAME if i < args.t_early else agg.AGG_BLOCK_SGA
+    t_end = args.layers - 1 if args.t_end is None else args.t_end
+    modes = [agg.AGG_BLOCK_FRAME if (i < args.t_early or i > t_end) else agg.AGG_BLOCK_SGA
              for i in range(args.layers)]
+    n_frame = sum(m == agg.AGG_BLOCK_FRAME for m in modes)
     nws = max(agg.agg_block_workspace_bytes(shape, m) for m in
               (agg.AGG_BLOCK_FRAME, agg.AGG_BLOCK_SGA, agg.AGG_BLOCK_DENSE))
     ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
@@ -342,7 +344,7 @@ def run_block(args, log):
     proj_flops = 4 * 2.0 * w.NQ * C * C
     fl_sga = sga_flops(w.NQ, M, w.H, w.D) + proj_flops
     fl_frame = 4.0 * w.N * w.L * w.L * w.D * w.H + proj_flops
-    fl_stack = args.t_early * fl_frame + (args.layers - args.t_early) * fl_sga
+    fl_stack = n_frame * fl_frame + (args.layers - n_frame) * fl_sga
     res = {
         "metric": "ms per aggregator pass over the global-attention blocks (LayerNorm + QKV "
                   "projection + attention + output projection + residual)",
@@ -350,9 +352,12 @@ def run_block(args, log):
         "ms_per_step": ms_stack, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s block stack: %d frames x (37x37+5) tokens, dim %d, %d global "
-                               "blocks, first %d as frame attention, rest subsampled with strides "
+                               "blocks, first %d%s as frame attention, rest subsampled with strides "
                                "(%d,%d), diag+mean" % (args.workload, w.N, C, args.layers,
-                                                       args.t_early, w.s_h, w.s_w),
+                                                       args.t_early,
+                                                       "" if args.t_end is None else
+                                                       " and those above index %d" % args.t_end,
+                                                       w.s_h, w.s_w),
                    "NQ": w.NQ, "M": M, "ms_block_sga": ms_sga, "ms_block_frame": ms_frame,
                    "ms_block_dense": ms_dense,
                    "tflops_block_sga": fl_sga / (ms_sga * 1e-3) / 1e12,
@@ -385,6 +390,9 @@ def main():
                     help="time the chained global-attention blocks (LayerNorm, projections, "
                          "attention, residual) on --workload instead of the bare attention path")
     ap.add_argument("--layers", type=int, default=12)
+    ap.add_argument("--t-end", type=int, default=None,
+                    help="with --block: blocks with index above this also run as per-frame attention "
+                         "(the paper's ablation on the last global layers); default: none")
     ap.add_argument("--t-early", type=int, default=4,
                     help="with --block: leading blocks run as per-frame attention")
     ap.add_argument("--data", choices=["structured", "iid", "zeros"], default="structured",
