@@ -612,3 +612,20 @@ def test_cell_mean_pooling(case):
     want_o, want_lse = lo.attn_over_rows(lshape(shape), qb, lo.round_to_bf16(kp),
                                          lo.round_to_bf16(vp), rows)
     check_output(buf.O, buf.lse, want_o, want_lse, rows, "cell mean")
+
+
+def test_list_path_with_extreme_logits():
+    """The general (running-maximum) path with membership taken from the bitmap: own key at
+    several hundred nats for every query, list chosen by the lowest-magnitude rule."""
+    shape = agg.make_shape(2, 3, 9, 7, 5, 3, 64, 2, 2, 1)
+    q, k, v = inputs.iid_qkv(2, shape.NQ, 3, 64, seed=4343, device="cuda")
+    q = (40.0 * k.float()).to(torch.bfloat16)
+    lst = harness.select(shape, agg.AGG_SELECT_LOW, 0, k)
+    from oracle import list_oracle as lo
+
+    buf = harness.list_forward(shape, lst, q, k, v, poison=True)
+    torch.cuda.synchronize()
+    rows = np.arange(shape.NQ, dtype=np.int64)
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    want_o, want_lse, _, _, _ = lo.attn_rows(lshape(shape), lst.cpu().numpy(), qb, kb, vb, rows)
+    check_output(buf.O, buf.lse, want_o, want_lse, rows, "list extreme", lse_rel=2.0 ** -7)
