@@ -8,6 +8,12 @@ the tensors the block DEFINES as bf16 -- the LayerNorm output, Q, K, V, the atte
 and y -- are rounded to bf16 (round to nearest even) where they are stored, exactly as the
 library's interface states.  Attention itself is `sga_oracle`.  Weights are given as float64
 arrays holding bf16-representable values; w_*: [C_out, C_in].
+
+Pins (tests/test_oracle_pins.py::test_block_oracle_pieces_and_composition): the bf16 rounding
+helper against torch's conversion incl. ties; LayerNorm and the linear map against
+torch.nn.functional in float64; the block with identity projections against x + Attn(LN x);
+the block with distinct random projections and biases against the formula written out with
+torch float64 ops and torch's scaled_dot_product_attention.
 """
 from __future__ import annotations
 

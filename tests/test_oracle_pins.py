@@ -554,6 +554,28 @@ def test_block_oracle_pieces_and_composition():
             o, _ = orc.dense_rows(shape, xn, xn, xn, rows)
         o = blk.from_bf16_bits(blk.to_bf16_bits(o)).reshape(1, shape.NQ, C)
         assert np.array_equal(y, blk.from_bf16_bits(blk.to_bf16_bits(x + o)))
+    # distinct random projections and biases, dense mode, against the formula written out with
+    # torch float64 ops (catches swapped projections, a transposed weight, a dropped bias or
+    # residual)
+    t = torch.from_numpy
+    rb = lambda a: blk.from_bf16_bits(blk.to_bf16_bits(a))
+    wts = dict(ln_gamma=1.0 + 0.1 * rng.standard_normal(C), ln_beta=0.1 * rng.standard_normal(C),
+               ln_eps=1e-6)
+    for name in "qkvo":
+        wts["w_" + name] = rb(rng.standard_normal((C, C)) / np.sqrt(C))
+        wts["b_" + name] = 0.05 * rng.standard_normal(C)
+    y = blk.block(shape, blk.DENSE, xb, wts)
+    x = t(blk.from_bf16_bits(xb))
+    xn = t(rb(torch.nn.functional.layer_norm(x, (C,), t(wts["ln_gamma"]), t(wts["ln_beta"]),
+                                             eps=1e-6).numpy()))
+    proj = {n: t(rb(torch.nn.functional.linear(xn, t(wts["w_" + n]), t(wts["b_" + n])).numpy()))
+            .view(1, shape.NQ, shape.H, shape.D).permute(0, 2, 1, 3) for n in "qkv"}
+    att = torch.nn.functional.scaled_dot_product_attention(proj["q"], proj["k"], proj["v"],
+                                                           scale=shape.scale)
+    att = t(rb(att.permute(0, 2, 1, 3).reshape(1, shape.NQ, C).numpy()))
+    want = rb((x + torch.nn.functional.linear(att, t(wts["w_o"]), t(wts["b_o"]))).numpy())
+    # float64 sums in a different order can flip a bf16 rounding on a handful of entries
+    assert (y != want).mean() < 2e-3 and np.abs(y - want).max() < 2.0 ** -6
 
 
 # ----------------------------------------------------------------------------
