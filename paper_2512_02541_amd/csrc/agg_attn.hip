@@ -68,11 +68,19 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #ifndef AGG_ORDER
 #define AGG_ORDER 0
 #endif
+#ifndef AGG_PAT
+#define AGG_PAT 1
+#endif
+#ifndef AGG_WAVES
+#define AGG_WAVES 4
+#endif
 
 constexpr int kQB = AGG_QB;             // 32-query blocks per wavefront
-constexpr int kAttnThreads = 256;
+constexpr int kWaves = AGG_WAVES;       // wavefronts per workgroup
+constexpr int kAttnThreads = 64 * kWaves;
 constexpr int kWaveQ = 32 * kQB;        // queries per wavefront
-constexpr int kQTile = 4 * kWaveQ;      // queries per workgroup
+constexpr int kQTile = kWaves * kWaveQ; // queries per workgroup
+constexpr int kBlocksPerCu = 8 / (kWaves * (kQB == 2 ? 1 : 2));  // two wavefronts per SIMD at kQB = 2
 constexpr int kXcds = 8;
 constexpr int kLdsTiles = 3;
 constexpr int kEpiStride = kHeadDim + 8;  // bf16 per query row of the epilogue's LDS tile (padded)
@@ -275,9 +283,33 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
     // issue order inside the step: one MFMA, then its share of the vector work
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
+#if AGG_PAT == 1
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
       __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+#elif AGG_PAT == 2
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+#elif AGG_PAT == 3
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+#elif AGG_PAT == 4
+      if (i % 2 == 0) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+      }
+#elif AGG_PAT == 5
+      // LDS fragment reads pinned right behind the MFMA that frees their registers
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (qb == 0 && (i == 3 || i == 7)) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+#endif
     }
     __builtin_amdgcn_sched_barrier(0);
 #elif AGG_SCHED == 2
@@ -291,7 +323,7 @@ template <bool kGen>
 __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const uint16_t* kc,
                                          const uint16_t* vc, int ntiles, int last_valid, int tid,
                                          int wave, int lane, int vlane, int g2) {
-  // this wavefront's share of a tile copy: chunks [64 wave, +64) and [256 + 64 wave, +64)
+  // this wavefront's share of a tile copy: 64 consecutive chunks per instruction
   const uint32_t voff0 = (uint32_t)tid * 16u;
   const uint32_t voff1 = voff0 + (uint32_t)kAttnThreads * 16u;
   const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
@@ -300,9 +332,9 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
     const uint32_t mk = wbase + (uint32_t)buf * (kChunks * 16);
     const uint32_t mv = wbase + (uint32_t)(kLdsTiles + buf) * (kChunks * 16);
     dma16(ksrc, voff0, mk);
-    dma16(ksrc, voff1, mk + kAttnThreads * 16);
+    if (kAttnThreads < kChunks) dma16(ksrc, voff1, mk + kAttnThreads * 16);
     dma16(vsrc, voff0, mv);
-    dma16(vsrc, voff1, mv + kAttnThreads * 16);
+    if (kAttnThreads < kChunks) dma16(vsrc, voff1, mv + kAttnThreads * 16);
   };
 
   copy_tile(kc, vc, 0);
@@ -373,7 +405,7 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
   return true;
 }
 
-__global__ __launch_bounds__(kAttnThreads, kQB == 2 ? 2 : 1) void sga_attn_kernel(
+__global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
     Geom g, uint32_t flags, float qscale, float mean_bias2, const uint16_t* __restrict__ Q,
     const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const uint16_t* __restrict__ Kc, const uint16_t* __restrict__ Vc,
@@ -553,50 +585,44 @@ __global__ __launch_bounds__(kAttnThreads, kQB == 2 ? 2 : 1) void sga_attn_kerne
 
   // ---- normalise and store ----
   // A lane holds four consecutive channels of one query per register group: stored from there,
-  // every instruction would scatter 8-byte pieces over 64 rows that lie 2*H*64 bytes apart.
-  // Each wavefront instead turns 64 x 64 pieces of its tile through a private part of the (now
-  // idle) K/V LDS and writes whole 128-byte (query, head) rows, eight per instruction.
+  // every instruction would scatter 8-byte pieces over 32 rows that lie 2*H*64 bytes apart.
+  // Each wavefront instead turns its tile, 32 queries at a time, through a private part of the
+  // (now idle) K/V LDS and writes whole 128-byte (query, head) rows, eight per instruction.
   __syncthreads();  // every wavefront is done with the K/V tiles
-  uint16_t* epi = smem + wave * (64 * kEpiStride);
+  uint16_t* epi = smem + wave * (32 * kEpiStride);
 #pragma unroll
-  for (int half = 0; half < kQB / 2; ++half) {
+  for (int qb = 0; qb < kQB; ++qb) {
+    const float l = l_fin[qb];
+    const float inv = 1.0f / l;
 #pragma unroll
-    for (int q2 = 0; q2 < 2; ++q2) {
-      const int qb = half * 2 + q2;
-      const float l = l_fin[qb];
-      const float inv = 1.0f / l;
+    for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int d0 = 32 * db + 8 * r4 + 4 * g2;
-          u32x2 o2;
-          o2[0] = pack_bf16(w.O[qb][db][r4 * 4 + 0] * inv, w.O[qb][db][r4 * 4 + 1] * inv);
-          o2[1] = pack_bf16(w.O[qb][db][r4 * 4 + 2] * inv, w.O[qb][db][r4 * 4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(epi + (q2 * 32 + l32) * kEpiStride + d0) = o2;
-        }
-      const int64_t q = q_wave + qb * 32 + l32;
-      if (lse && g2 == 0 && q < g.NQ)
-        lse[((int64_t)b * g.H + h) * g.NQ + q] = (m_fin[qb] + log2f(l)) * kLn2;
-    }
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int d0 = 32 * db + 8 * r4 + 4 * g2;
+        u32x2 o2;
+        o2[0] = pack_bf16(w.O[qb][db][r4 * 4 + 0] * inv, w.O[qb][db][r4 * 4 + 1] * inv);
+        o2[1] = pack_bf16(w.O[qb][db][r4 * 4 + 2] * inv, w.O[qb][db][r4 * 4 + 3] * inv);
+        *reinterpret_cast<u32x2*>(epi + l32 * kEpiStride + d0) = o2;
+      }
+    const int64_t q0 = q_wave + qb * 32;
+    if (lse && g2 == 0 && q0 + l32 < g.NQ)
+      lse[((int64_t)b * g.H + h) * g.NQ + q0 + l32] = (m_fin[qb] + log2f(l)) * kLn2;
     // the wavefront's own writes, read back by other lanes of the same wavefront
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 4; ++i) {
       const int row = i * 8 + (lane >> 3);
-      const int64_t q = q_wave + half * 64 + row;
+      const int64_t q = q0 + row;
       const u32x4 o4 = *reinterpret_cast<const u32x4*>(epi + row * kEpiStride + (lane & 7) * 8);
       if (q < g.NQ)
         *reinterpret_cast<u32x4*>(O + (((int64_t)b * g.NQ + q) * g.H + h) * kHeadDim +
                                   (lane & 7) * 8) = o4;
     }
-    if (half + 1 < kQB / 2) {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
   }
 }
 
