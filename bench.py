@@ -197,6 +197,8 @@ def run_only(args, log):
         q, k, v = inputs.iid_qkv(w.B, w.NQ, w.H, w.D, w.seed, "cuda")
     else:
         q, k, v = inputs.make_qkv(w, "cuda")
+        if args.data == "extreme":  # one query in 256 with logits far outside the fast path's
+            q[:, ::256] *= 64.0     # window: every workgroup falls back to the general path
     buf = harness.alloc(shape, "cuda")
     harness.subsample(buf, k, v)
     torch.cuda.synchronize()
@@ -395,7 +397,7 @@ def main():
                          "(the paper's ablation on the last global layers); default: none")
     ap.add_argument("--t-early", type=int, default=4,
                     help="with --block: leading blocks run as per-frame attention")
-    ap.add_argument("--data", choices=["structured", "iid", "zeros"], default="structured",
+    ap.add_argument("--data", choices=["structured", "iid", "zeros", "extreme"], default="structured",
                     help="with --only: values of Q/K/V (zeros shows what the same instruction stream "
                          "reaches when the operands do not toggle)")
     ap.add_argument("--only", choices=["attn", "gather", "dense", "copy"], default=None,

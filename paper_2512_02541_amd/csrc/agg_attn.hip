@@ -32,14 +32,15 @@
 //     invariant to the reference, float/bf16 exponents cover 2^+-126, and the
 //     per-score work shrinks to exp + convert + add.  A row whose sum leaves
 //     [2^-90, 2^90] (logits beyond about +-60 nats) makes the whole workgroup
-//     redo its rows in the general path; ordinary attention logits never get
-//     there.  The sums are checked every few tiles, so an overflow ends the
-//     fast pass early.
-//   * General path: the same pipeline with a per-row reference.  The reference
-//     enters as the (negative) initial accumulator of the score MFMA, so
-//     subtracting it is free; it is raised lazily -- only when a unit's maximum
-//     exceeds it by more than 2^60 -- so the rescaling of the accumulator is a
-//     rare, wavefront-uniform branch instead of per-unit work.
+//     redo its rows in the general path (a second kernel behind this one, see
+//     the end of the file); ordinary attention logits never get there.  The
+//     sums are checked every few tiles, so an overflow ends the fast pass early.
+//   * General path: the same pipeline with a per-row reference that is subtracted
+//     before the exponential.  The reference starts at the largest of the extras
+//     and the first 32 keys and is raised lazily: a unit's row sums show when a
+//     score exceeds it by more than 2^100; only then (a rare, wavefront-uniform
+//     branch) is the unit's maximum taken, the accumulator rescaled and the
+//     unit redone.  No running maximum is computed otherwise.
 //   * The zero-padded rows of the last tile are masked there (the last tile is
 //     peeled), nowhere else.
 //   * The extras enter as the initial state (sum, accumulator) of either path, so
@@ -62,15 +63,6 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #ifndef AGG_QB
 #define AGG_QB 2
 #endif
-#ifndef AGG_SCHED
-#define AGG_SCHED 1
-#endif
-#ifndef AGG_ORDER
-#define AGG_ORDER 0
-#endif
-#ifndef AGG_PAT
-#define AGG_PAT 1
-#endif
 #ifndef AGG_WAVES
 #define AGG_WAVES 4
 #endif
@@ -90,6 +82,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSumHi = 1.2379400392853803e27f;   // 2^90
 constexpr float kSumLo = 8.077935669463161e-28f;   // 2^-90
 constexpr float kLazy = 60.0f;  // general path: a unit may exceed the row's reference by 2^60
+constexpr float kUnitHi = 1.2676506002282294e30f;  // 2^100: a unit's row sum that forces a look
 
 union Frag {
   u32x4 u;
@@ -139,6 +132,13 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t 
                : "v"(voff), "s"(base), "s"(m0)
                : "memory");
 }
+// a pointer every lane agrees on, as two scalar registers (what the copy's base operand needs)
+__device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* q) {
+  const uint64_t v = (uint64_t)(uintptr_t)q;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const uint16_t*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 
 #define AGG_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a).h, (b).h, (c), 0, 0, 0)
@@ -171,7 +171,6 @@ struct Wave {
   Frag Qf[kQB][4];     // B operand of S^T = K Q^T, pre-multiplied by scale*log2(e)
   f32x16 O[kQB][2];    // O^T accumulator; channel = 32 db + 8 (r/4) + 4 g2 + r%4
   f32x16 S[kQB];       // score tiles in flight
-  f32x16 C[kQB];       // general path: minus the row's reference, the score MFMA's initial value
   float la[kQB][2];    // two partial row sums per query block
   float mref[kQB];     // general path: the row's reference (base-2 logit)
   Frag a[4];           // K fragments of the 32-key block whose scores are being computed
@@ -210,29 +209,13 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
     const bool do_qk = !(kLast && beyond);
     f32x16 Sn;
     if (do_qk) {
-      if (kGen) {
-        Sn = AGG_MFMA(w.a[0], w.Qf[tq][0], w.C[tq]);
-      } else {
-        f32x16 z;
+      f32x16 z;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) z[r] = 0.f;
-        Sn = AGG_MFMA(w.a[0], w.Qf[tq][0], z);
-      }
-    }
-#if AGG_ORDER == 1
-    w.O[pq][0] = AGG_MFMA(w.v[0], w.P[0], w.O[pq][0]);
-    if (do_qk) Sn = AGG_MFMA(w.a[1], w.Qf[tq][1], Sn);
-    w.O[pq][1] = AGG_MFMA(w.v[1], w.P[0], w.O[pq][1]);
-    if (do_qk) Sn = AGG_MFMA(w.a[2], w.Qf[tq][2], Sn);
-    w.O[pq][0] = AGG_MFMA(w.v[2], w.P[1], w.O[pq][0]);
-    if (do_qk) Sn = AGG_MFMA(w.a[3], w.Qf[tq][3], Sn);
-    w.O[pq][1] = AGG_MFMA(w.v[3], w.P[1], w.O[pq][1]);
-#else
-    if (do_qk) {
+      for (int r = 0; r < 16; ++r) z[r] = 0.f;
+      Sn = AGG_MFMA(w.a[0], w.Qf[tq][0], z);
 #pragma unroll
       for (int ks = 1; ks < 4; ++ks) Sn = AGG_MFMA(w.a[ks], w.Qf[tq][ks], Sn);
     }
-#endif
     if (tq == kQB - 1) {  // that was the block's last unit: fragments of the following block
       if (un / kQB == 0) load_k_frags(lds, cur, 1, lane, w.a);
       else if (!kLast) load_k_frags(lds, nxt, 0, lane, w.a);
@@ -243,78 +226,72 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
     {
       f32x16& S = w.S[qb];
       if (kLast && valid < kTileRows) mask16(S, kb, valid, g2);
-      if (kGen) {
-        float mx = fmaxf(fmaxf(S[0], S[1]), S[2]);
+      if (!kGen) {
+        exp16(S, Pn, w.la[qb][0], w.la[qb][1]);
+      } else {
+        // probabilities relative to the row's reference; the unit's own sums tell whether the
+        // reference still holds (a score more than 2^100 above it cannot hide in them)
 #pragma unroll
-        for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, S[r]), S[r + 1]);
-        mx = fmaxf(mx, S[15]);
-        mx = pair_max(mx);
-        if (__builtin_amdgcn_ballot_w64(mx > kLazy) != 0) {
-          // raise the reference of the rows that need it; exact for the others (factor 1)
+        for (int r = 0; r < 16; ++r) S[r] -= w.mref[qb];
+        float u0 = 0.f, u1 = 0.f;
+        exp16(S, Pn, u0, u1);
+        if (__builtin_amdgcn_ballot_w64(!(u0 + u1 < kUnitHi)) != 0) {
+          // rare: recompute the unit's scores from the tile (still resident), raise the reference
+          // of the rows that need it (factor 1 for the others), scale what they have accumulated,
+          // and redo the unit
+          f32x16 R;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) R[r] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) {
+            Frag kf;
+            kf.u = lds[cur * kChunks + (kb * 4 + ks) * 64 + lane];
+            R = AGG_MFMA(kf, w.Qf[qb][ks], R);
+          }
+          if (kLast && valid < kTileRows) mask16(R, kb, valid, g2);
+          float mx = R[0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, R[r]);
+          mx = pair_max(mx) - w.mref[qb];
           const float d = mx > kLazy ? mx : 0.f;
           const float f = fast_exp2(-d);
           w.mref[qb] += d;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            S[r] -= d;
-            w.C[qb][r] = -w.mref[qb];
+            R[r] -= w.mref[qb];
             w.O[qb][0][r] *= f;
             w.O[qb][1][r] *= f;
           }
           w.la[qb][0] *= f;
           w.la[qb][1] *= f;
+          u0 = 0.f;
+          u1 = 0.f;
+          exp16(R, Pn, u0, u1);
         }
+        w.la[qb][0] += u0;
+        w.la[qb][1] += u1;
       }
-      exp16(S, Pn, w.la[qb][0], w.la[qb][1]);
     }
     if (do_qk) w.S[tq] = Sn;
 
     // ---- matrix core, part 2: P V of unit sg - 1 ----
-#if AGG_ORDER != 1
     w.O[pq][0] = AGG_MFMA(w.v[0], w.P[0], w.O[pq][0]);
     w.O[pq][1] = AGG_MFMA(w.v[1], w.P[0], w.O[pq][1]);
     w.O[pq][0] = AGG_MFMA(w.v[2], w.P[1], w.O[pq][0]);
     w.O[pq][1] = AGG_MFMA(w.v[3], w.P[1], w.O[pq][1]);
-#endif
     if (qb == 0) load_v_frags(lds, cur, kb, vlane, w.v);  // the previous block is done with them
     w.P[0] = Pn[0];
     w.P[1] = Pn[1];
-#if AGG_SCHED == 1
-    // issue order inside the step: one MFMA, then its share of the vector work
+    // Issue order inside the step: one MFMA, then its share of the vector work (two
+    // exponentials, one conversion, two additions).  Left to itself the scheduler bunches the
+    // MFMAs, and the wavefront then stalls on the matrix pipe with vector work still to issue.
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-#if AGG_PAT == 1
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-#elif AGG_PAT == 2
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-#elif AGG_PAT == 3
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
-#elif AGG_PAT == 4
-      if (i % 2 == 0) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
-      }
-#elif AGG_PAT == 5
-      // LDS fragment reads pinned right behind the MFMA that frees their registers
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (qb == 0 && (i == 3 || i == 7)) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-#endif
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);  // transcendental
+      __builtin_amdgcn_sched_group_barrier(0x002, kGen ? 5 : 3, 0);  // other vector ALU
     }
     __builtin_amdgcn_sched_barrier(0);
-#elif AGG_SCHED == 2
-    __builtin_amdgcn_sched_barrier(0);
-#endif
   }
 }
 
@@ -351,12 +328,8 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
 #pragma unroll
   for (int qb = 0; qb + 1 < kQB; ++qb) {
     f32x16 s;
-    if (kGen) {
-      s = w.C[qb];
-    } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
-    }
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) s = AGG_MFMA(w.a[ks], w.Qf[qb][ks], s);
     w.S[qb] = s;
@@ -405,16 +378,28 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
   return true;
 }
 
-__global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
-    Geom g, uint32_t flags, float qscale, float mean_bias2, const uint16_t* __restrict__ Q,
-    const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const uint16_t* __restrict__ Kc, const uint16_t* __restrict__ Vc,
-    const float* __restrict__ kmean, const float* __restrict__ vmean, uint16_t* __restrict__ O,
-    float* __restrict__ lse, int nqt, int npairs, const uint32_t* __restrict__ kept_bits,
-    const int32_t* __restrict__ nd_dev) {
-  __shared__ __align__(16) uint16_t smem[2 * kLdsTiles * kTileElems];  // K tiles, then V tiles
-  u32x4* lds = reinterpret_cast<u32x4*>(smem);
+// Kernel arguments.
+struct AttnArgs {
+  Geom g;
+  uint32_t flags;
+  float qscale, mean_bias2;  // scale*log2(e), mean_logit_bias*log2(e)
+  const uint16_t *Q, *K, *V, *Kc, *Vc;
+  const float *kmean, *vmean;
+  uint16_t* O;
+  float* lse;
+  int nqt, npairs;
+  const uint32_t* kept_bits;
+  const int32_t* nd_dev;
+};
 
+__shared__ __align__(16) uint16_t smem[2 * kLdsTiles * kTileElems];  // K tiles, then V tiles
+
+// One workgroup's rows by one of the two paths.  Returns false, without storing anything, when
+// the fast path met a row it cannot handle.
+template <bool kGen>
+__device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) {
+  const Geom& g = p.g;
+  u32x4* lds = reinterpret_cast<u32x4*>(smem);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -422,30 +407,20 @@ __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
   const int g2 = lane >> 5;
   const int vlane = g2 * 64 + l32;
 
-  // workgroup -> ((batch, head) pair, query tile); consecutive ids go to consecutive XCDs
-  const int bid = blockIdx.x;
-  const int xcd = bid % kXcds;
-  const int seq = bid / kXcds;
-  const int pair = (seq / nqt) * kXcds + xcd;
-  const int qt = seq % nqt;
-  if (pair >= npairs) return;  // uniform for the whole workgroup, before any barrier
-  const int b = pair / g.H;
-  const int h = pair % g.H;
-
   const int ntiles = (int)(g.M_pad / kTileRows);
   const int last_valid = (int)(g.M - (int64_t)(ntiles - 1) * kTileRows);  // 1..64
   const int64_t bh_off = ((int64_t)b * g.H + h) * g.M_pad * kHeadDim;
-  const uint16_t* kc = Kc + bh_off;
-  const uint16_t* vc = Vc + bh_off;
+  const uint16_t* kc = uniform_ptr(p.Kc + bh_off);
+  const uint16_t* vc = uniform_ptr(p.Vc + bh_off);
 
   Wave w;
   bool dropped[kQB];
   float l_self[kQB], l_mean[kQB];  // base-2 logits of the extras (-inf when absent)
   // caller's list: membership comes from a bitmap, the dropped count from device memory
-  const int64_t n_drop = nd_dev ? (int64_t)nd_dev[b] : g.n_dropped;
-  const bool use_mean = (flags & AGG_MEAN) && n_drop > 0;
-  const bool use_diag = (flags & AGG_DIAG) && (kept_bits != nullptr || n_drop > 0);
-  const uint32_t* kbits = kept_bits ? kept_bits + (int64_t)b * ((g.NQ + 31) / 32) : nullptr;
+  const int64_t n_drop = p.nd_dev ? (int64_t)p.nd_dev[b] : g.n_dropped;
+  const bool use_mean = (p.flags & AGG_MEAN) && n_drop > 0;
+  const bool use_diag = (p.flags & AGG_DIAG) && (p.kept_bits != nullptr || n_drop > 0);
+  const uint32_t* kbits = p.kept_bits ? p.kept_bits + (int64_t)b * ((g.NQ + 31) / 32) : nullptr;
   const int64_t q_wave = (int64_t)qt * kQTile + wave * kWaveQ;
 
   // ---- Q fragments and the logits of the extras ----
@@ -456,17 +431,17 @@ __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
     const int64_t qbase = (((int64_t)b * g.NQ + qc) * g.H + h) * kHeadDim;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      u32x4 raw = *reinterpret_cast<const u32x4*>(Q + qbase + ks * 16 + g2 * 8);
+      u32x4 raw = *reinterpret_cast<const u32x4*>(p.Q + qbase + ks * 16 + g2 * 8);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        w.Qf[qb][ks].u[i] = pack_bf16(bf16_lo(raw[i]) * qscale, bf16_hi(raw[i]) * qscale);
+        w.Qf[qb][ks].u[i] = pack_bf16(bf16_lo(raw[i]) * p.qscale, bf16_hi(raw[i]) * p.qscale);
     }
     // lanes l and l^32 hold the two halves of the channel range
     dropped[qb] = use_diag && q < g.NQ &&
                   (kbits ? ((kbits[q >> 5] >> (q & 31)) & 1u) == 0u : (bool)token_is_dropped(g, q));
     float dot_self = 0.f, dot_mean = 0.f;
     if (use_mean || use_diag) {
-      const float* km = kmean + ((int64_t)b * g.H + h) * kHeadDim;
+      const float* km = p.kmean + ((int64_t)b * g.H + h) * kHeadDim;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         const int d0 = ks * 16 + g2 * 8;
@@ -483,17 +458,17 @@ __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
           for (int i = 0; i < 4; ++i) dot_mean += qv[i] * c0[i] + qv[4 + i] * c1[i];
         }
         if (dropped[qb]) {
-          u32x4 kr = *reinterpret_cast<const u32x4*>(K + qbase + d0);
+          u32x4 kr = *reinterpret_cast<const u32x4*>(p.K + qbase + d0);
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             dot_self += qv[2 * i] * bf16_lo(kr[i]) + qv[2 * i + 1] * bf16_hi(kr[i]);
         }
       }
     }
-    dot_self += __shfl_xor(dot_self, 32);
-    dot_mean += __shfl_xor(dot_mean, 32);
+    dot_self = pair_sum(dot_self);
+    dot_mean = pair_sum(dot_mean);
     l_self[qb] = dropped[qb] ? dot_self : -INFINITY;
-    l_mean[qb] = use_mean ? dot_mean + mean_bias2 : -INFINITY;
+    l_mean[qb] = use_mean ? dot_mean + p.mean_bias2 : -INFINITY;
   }
 
   // Initial state = extras weighted by exp2(logit - m0):  O0[d] = w_self v_i[d] + w_mean vmean[d]
@@ -505,7 +480,7 @@ __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
     const int64_t q = q_wave + qb * 32 + l32;
     const int64_t qc = q < g.NQ ? q : g.NQ - 1;
     const int64_t qbase = (((int64_t)b * g.NQ + qc) * g.H + h) * kHeadDim;
-    const float* vm = vmean + ((int64_t)b * g.H + h) * kHeadDim;
+    const float* vm = p.vmean + ((int64_t)b * g.H + h) * kHeadDim;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -517,7 +492,7 @@ __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
           acc = mv * w_mean;
         }
         if (dropped[qb]) {
-          u32x2 vr = *reinterpret_cast<const u32x2*>(V + qbase + d0);
+          u32x2 vr = *reinterpret_cast<const u32x2*>(p.V + qbase + d0);
           acc[0] += w_self * bf16_lo(vr[0]);
           acc[1] += w_self * bf16_hi(vr[0]);
           acc[2] += w_self * bf16_lo(vr[1]);
@@ -528,59 +503,49 @@ __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
       }
   };
 
-  float m_fin[kQB], l_fin[kQB];
-
-  // =============================== fast path ===============================
+  if (!kGen) {
 #pragma unroll
-  for (int qb = 0; qb < kQB; ++qb) init_extras(qb, 0.f);
-  bool ok = key_loop<false>(w, lds, kc, vc, ntiles, last_valid, tid, wave, lane, vlane, g2);
+    for (int qb = 0; qb < kQB; ++qb) init_extras(qb, 0.f);
+  } else {
+    // reference: the largest of the extras and of the first 32 keys (row 0 always exists),
+    // whose fragments come straight from global memory here
+    const u32x4* k4 = reinterpret_cast<const u32x4*>(kc);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) w.a[ks].u = k4[ks * 64 + lane];
+    const int valid0 = ntiles == 1 ? last_valid : kTileRows;
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) {
+      f32x16 s;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) s = AGG_MFMA(w.a[ks], w.Qf[qb][ks], s);
+      if (valid0 < 32) mask16(s, 0, valid0, g2);
+      float mx = s[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+      mx = pair_max(mx);
+      mx = fmaxf(mx, fmaxf(l_self[qb], l_mean[qb]));
+      // a NaN or infinite score cannot serve as reference; the row's result is NaN anyway
+      if (!(fabsf(mx) < 3.0e38f)) mx = 0.f;
+      w.mref[qb] = mx;
+      init_extras(qb, mx);
+    }
+  }
+
+  const bool done =
+      key_loop<kGen>(w, lds, kc, vc, ntiles, last_valid, tid, wave, lane, vlane, g2);
+  float l_fin[kQB];
   bool unsafe = false;
 #pragma unroll
   for (int qb = 0; qb < kQB; ++qb) {
-    const float lp = w.la[qb][0] + w.la[qb][1];
-    l_fin[qb] = pair_sum(lp);
-    m_fin[qb] = 0.f;
+    l_fin[qb] = pair_sum(w.la[qb][0] + w.la[qb][1]);
     // a sum outside [2^-90, 2^90] (or NaN): the unreferenced exponentials were not safe
     unsafe = unsafe || !(l_fin[qb] < kSumHi) || !(l_fin[qb] > kSumLo);
   }
-  if (!ok || __syncthreads_or(unsafe ? 1 : 0)) {
-    // ============================= general path =============================
-    __syncthreads();  // every wavefront has left the fast pass's tiles
-    // reference: the largest of the extras and the first 32 keys (row 0 always exists)
-    {
-      // the first key block, straight from global memory in fragment order
-      const u32x4* k4 = reinterpret_cast<const u32x4*>(kc);
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) w.a[ks].u = k4[ks * 64 + lane];
-      const int valid0 = ntiles == 1 ? last_valid : kTileRows;
-#pragma unroll
-      for (int qb = 0; qb < kQB; ++qb) {
-        f32x16 s;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) s = AGG_MFMA(w.a[ks], w.Qf[qb][ks], s);
-        if (valid0 < 32) mask16(s, 0, valid0, g2);
-        float mx = s[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-        mx = pair_max(mx);
-        mx = fmaxf(mx, fmaxf(l_self[qb], l_mean[qb]));
-        // a NaN or infinite score cannot serve as reference; the row's result is NaN anyway
-        if (!(fabsf(mx) < 3.0e38f)) mx = 0.f;
-        w.mref[qb] = mx;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) w.C[qb][r] = -mx;
-        init_extras(qb, mx);
-      }
-    }
-    key_loop<true>(w, lds, kc, vc, ntiles, last_valid, tid, wave, lane, vlane, g2);
-#pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) {
-      const float lp = w.la[qb][0] + w.la[qb][1];
-      l_fin[qb] = pair_sum(lp);
-      m_fin[qb] = w.mref[qb];
-    }
+  if (!kGen) {
+    if (!done) return false;  // uniform: decided by a workgroup-wide vote inside the loop
+    if (__syncthreads_or(unsafe ? 1 : 0)) return false;
   }
 
   // ---- normalise and store ----
@@ -605,8 +570,9 @@ __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
         *reinterpret_cast<u32x2*>(epi + l32 * kEpiStride + d0) = o2;
       }
     const int64_t q0 = q_wave + qb * 32;
-    if (lse && g2 == 0 && q0 + l32 < g.NQ)
-      lse[((int64_t)b * g.H + h) * g.NQ + q0 + l32] = (m_fin[qb] + log2f(l)) * kLn2;
+    if (p.lse && g2 == 0 && q0 + l32 < g.NQ)
+      p.lse[((int64_t)b * g.H + h) * g.NQ + q0 + l32] =
+          ((kGen ? w.mref[qb] : 0.f) + log2f(l)) * kLn2;
     // the wavefront's own writes, read back by other lanes of the same wavefront
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
     __builtin_amdgcn_wave_barrier();
@@ -617,13 +583,55 @@ __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(
       const int64_t q = q0 + row;
       const u32x4 o4 = *reinterpret_cast<const u32x4*>(epi + row * kEpiStride + (lane & 7) * 8);
       if (q < g.NQ)
-        *reinterpret_cast<u32x4*>(O + (((int64_t)b * g.NQ + q) * g.H + h) * kHeadDim +
+        *reinterpret_cast<u32x4*>(p.O + (((int64_t)b * g.NQ + q) * g.H + h) * kHeadDim +
                                   (lane & 7) * 8) = o4;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
   }
+  return true;
+}
+
+// A workgroup whose fast pass failed leaves this pattern (four bf16 NaNs with distinct payloads)
+// in the first four channels of its first output row and stores nothing else; the second kernel
+// redoes exactly the workgroups that carry it.  Should a correct result ever equal the pattern,
+// the second kernel recomputes that workgroup, which is harmless.
+constexpr uint64_t kRedoMark = 0x7F997FC37FA57FC1ull;
+
+__device__ __forceinline__ uint64_t* redo_slot(const AttnArgs& p, int b, int h, int qt) {
+  return reinterpret_cast<uint64_t*>(p.O + (((int64_t)b * p.g.NQ + (int64_t)qt * kQTile) * p.g.H + h) *
+                                               kHeadDim);
+}
+
+// workgroup -> ((batch, head) pair, query tile); consecutive ids go to consecutive XCDs
+__device__ __forceinline__ bool workgroup_tile(const AttnArgs& p, int& b, int& h, int& qt) {
+  const int bid = blockIdx.x;
+  const int xcd = bid % kXcds;
+  const int seq = bid / kXcds;
+  const int pair = (seq / p.nqt) * kXcds + xcd;
+  qt = seq % p.nqt;
+  if (pair >= p.npairs) return false;  // uniform for the whole workgroup
+  b = pair / p.g.H;
+  h = pair % p.g.H;
+  return true;
+}
+
+__global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(AttnArgs p) {
+  int b, h, qt;
+  if (!workgroup_tile(p, b, h, qt)) return;
+  if (!attend<false>(p, b, h, qt) && threadIdx.x == 0) *redo_slot(p, b, h, qt) = kRedoMark;
+}
+
+// The general path is a kernel of its own, launched behind the first on the same stream: it is
+// rarely needed, starts over from the workgroup's inputs, and this way does not weigh on the
+// register allocation of the fast path.  Workgroups without the mark leave at once.
+__global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_general_kernel(AttnArgs p) {
+  int b, h, qt;
+  if (!workgroup_tile(p, b, h, qt)) return;
+  if (*redo_slot(p, b, h, qt) != kRedoMark) return;  // same value in every lane
+  __syncthreads();  // every wavefront has read the mark before any of them overwrites it
+  attend<true>(p, b, h, qt);
 }
 
 hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bias, const void* Q,
@@ -635,10 +643,26 @@ hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bi
   const int64_t groups = (int64_t)((npairs + kXcds - 1) / kXcds) * kXcds * nqt;
   if (groups > 0x7FFFFFFF) return hipErrorInvalidConfiguration;
   (void)hipGetLastError();  // drop any stale error so the check below is this launch's
-  hipLaunchKernelGGL(sga_attn_kernel, dim3((unsigned)groups), dim3(kAttnThreads), 0, st, g, flags,
-                     scale * kLog2e, mean_bias * kLog2e, (const uint16_t*)Q, (const uint16_t*)K,
-                     (const uint16_t*)V, (const uint16_t*)Kc, (const uint16_t*)Vc, kmean, vmean,
-                     (uint16_t*)O, lse, nqt, npairs, kept_bits, nd_dev);
+  AttnArgs p;
+  p.g = g;
+  p.flags = flags;
+  p.qscale = scale * kLog2e;
+  p.mean_bias2 = mean_bias * kLog2e;
+  p.Q = (const uint16_t*)Q;
+  p.K = (const uint16_t*)K;
+  p.V = (const uint16_t*)V;
+  p.Kc = (const uint16_t*)Kc;
+  p.Vc = (const uint16_t*)Vc;
+  p.kmean = kmean;
+  p.vmean = vmean;
+  p.O = (uint16_t*)O;
+  p.lse = lse;
+  p.nqt = nqt;
+  p.npairs = npairs;
+  p.kept_bits = kept_bits;
+  p.nd_dev = nd_dev;
+  hipLaunchKernelGGL(sga_attn_kernel, dim3((unsigned)groups), dim3(kAttnThreads), 0, st, p);
+  hipLaunchKernelGGL(sga_attn_general_kernel, dim3((unsigned)groups), dim3(kAttnThreads), 0, st, p);
   return hipGetLastError();
 }
 
