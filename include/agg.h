@@ -15,7 +15,8 @@
  *     otherwise patch p = t - n_special at grid row p / n_w, column p % n_w.
  *   - Q, K, V, O: bf16, device memory, contiguous [B, N*L, H, D] (token-major:
  *     what a fused QKV projection writes and an output projection reads).
- *   - D must be 64.  Pointers to bf16 tensors must be 16-byte aligned.
+ *   - D must be 64.  Pointers to bf16 tensors, to workspaces and to kmean/vmean must be
+ *     16-byte aligned; index, count, bitmap and lse pointers 4-byte aligned.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Every call only enqueues work on that stream: no allocation, no
  *     synchronisation, no retained pointers.  The caller owns every buffer.

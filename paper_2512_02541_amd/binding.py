@@ -16,6 +16,8 @@ LIB_PATH = os.environ.get("AGG_LIBRARY_PATH") or os.path.join(_HERE, "libagg.so"
 AGG_DIAG = 1
 AGG_MEAN = 2
 AGG_OK = 0
+AGG_ERR_NULL, AGG_ERR_SHAPE, AGG_ERR_UNSUPPORTED, AGG_ERR_ALIGN = -1, -2, -3, -4
+AGG_ERR_WORKSPACE, AGG_ERR_OVERFLOW, AGG_ERR_LAUNCH = -5, -6, -7
 
 
 class AggError(RuntimeError):

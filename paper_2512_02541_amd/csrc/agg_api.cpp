@@ -155,7 +155,7 @@ int agg_kv_subsample(const agg_shape* shape, const void* K, const void* V, void*
   if (rc != AGG_OK) return rc;
   if (!K || !V || !Kc || !Vc || !kmean || !vmean || !workspace) return AGG_ERR_NULL;
   if (misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) || misaligned(workspace) ||
-      ((uintptr_t)kmean & 3u) || ((uintptr_t)vmean & 3u) || ((uintptr_t)idx & 3u))
+      misaligned(kmean) || misaligned(vmean) || ((uintptr_t)idx & 3u))
     return AGG_ERR_ALIGN;
   if (workspace_bytes < agg_workspace_bytes(shape)) return AGG_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -172,8 +172,7 @@ int agg_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, co
   if (rc != AGG_OK) return rc;
   if (!Q || !K || !V || !Kc || !Vc || !kmean || !vmean || !O) return AGG_ERR_NULL;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) ||
-      misaligned(O) || ((uintptr_t)kmean & 15u) || ((uintptr_t)vmean & 15u) ||
-      ((uintptr_t)lse & 3u))
+      misaligned(O) || misaligned(kmean) || misaligned(vmean) || ((uintptr_t)lse & 3u))
     return AGG_ERR_ALIGN;
   hipStream_t st = (hipStream_t)hip_stream;
   if (launch_attn(g, shape->flags, shape->scale, shape->mean_logit_bias, Q, K, V, Kc, Vc, kmean,
@@ -296,7 +295,7 @@ int agg_kv_subsample_list(const agg_shape* shape, const int32_t* list, int64_t M
   if (!list || !K || !V || !Kc || !Vc || !kmean || !vmean || !kept_bits || !n_dropped || !workspace)
     return AGG_ERR_NULL;
   if (misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) || misaligned(workspace) ||
-      ((uintptr_t)kmean & 3u) || ((uintptr_t)vmean & 3u) || ((uintptr_t)list & 3u) ||
+      misaligned(kmean) || misaligned(vmean) || ((uintptr_t)list & 3u) ||
       ((uintptr_t)kept_bits & 3u) || ((uintptr_t)n_dropped & 3u))
     return AGG_ERR_ALIGN;
   if (workspace_bytes < list_workspace_bytes(g)) return AGG_ERR_WORKSPACE;
@@ -316,8 +315,8 @@ int agg_global_attn_fwd_list(const agg_shape* shape, int64_t M_list, const void*
   if (!Q || !K || !V || !Kc || !Vc || !kmean || !vmean || !kept_bits || !n_dropped || !O)
     return AGG_ERR_NULL;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) ||
-      misaligned(O) || ((uintptr_t)kmean & 15u) || ((uintptr_t)vmean & 15u) ||
-      ((uintptr_t)lse & 3u) || ((uintptr_t)kept_bits & 3u) || ((uintptr_t)n_dropped & 3u))
+      misaligned(O) || misaligned(kmean) || misaligned(vmean) || ((uintptr_t)lse & 3u) ||
+      ((uintptr_t)kept_bits & 3u) || ((uintptr_t)n_dropped & 3u))
     return AGG_ERR_ALIGN;
   if (launch_attn(g, shape->flags, shape->scale, shape->mean_logit_bias, Q, K, V, Kc, Vc, kmean,
                   vmean, O, lse, (hipStream_t)hip_stream, kept_bits, n_dropped) != hipSuccess)
