@@ -117,6 +117,22 @@ int agg_kv_subsample(const agg_shape* shape, const void* K, const void* V, void*
                      size_t workspace_bytes, void* hip_stream);
 
 /*
+ * agg_kv_subsample for callers that cannot allocate device memory and so cannot bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and bit-identical results, minus the workspace: the
+ * partial sums of the mean go to a device array that is part of the library (each GPU the
+ * library runs on holds agg_static_scratch_bytes() = 32 MiB of it until the process ends).
+ * The call allocates nothing.  Shapes whose agg_workspace_bytes() exceeds
+ * agg_static_scratch_bytes() are refused with AGG_ERR_WORKSPACE before anything is launched.
+ * The first call on a device looks the array's address up (with that device current, which it
+ * must be for every call).  All calls on one GPU share the array: two calls whose work may
+ * overlap on that GPU (different streams) race; calls on one stream do not.
+ */
+size_t agg_static_scratch_bytes(void);
+int agg_kv_subsample_static(const agg_shape* shape, const void* K, const void* V, void* Kc,
+                            void* Vc, int32_t* idx, float* kmean, float* vmean, void* hip_stream);
+
+/*
  * Sec. 4.3, the attention itself.  For every query i of every (batch, head):
  *   softmax over { scale*<q_i, Kc[m]> : m < M }
  *                u { scale*<q_i, k_i> }                    if AGG_DIAG and token i was dropped

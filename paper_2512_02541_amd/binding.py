@@ -66,6 +66,7 @@ EXPORTS = [
     "agg_block_workspace_bytes", "agg_global_block_fwd",
     "agg_select_kv_indices", "agg_list_compact_bytes", "agg_list_workspace_bytes",
     "agg_kv_subsample_list", "agg_global_attn_fwd_list", "agg_kv_pool",
+    "agg_static_scratch_bytes", "agg_kv_subsample_static",
 ]
 
 AGG_SELECT_FIRST = 0
@@ -147,6 +148,9 @@ def lib():
     L.agg_global_attn_fwd_list.argtypes = [shp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                            vp, vp, vp]
     L.agg_kv_pool.argtypes = [shp, vp, vp, vp, vp, vp]
+    L.agg_static_scratch_bytes.restype = ctypes.c_size_t
+    L.agg_static_scratch_bytes.argtypes = []
+    L.agg_kv_subsample_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp]
     _lib = L
     return L
 
@@ -240,6 +244,16 @@ def agg_kv_subsample(shape, K, V, Kc, Vc, idx, kmean, vmean, workspace, workspac
     _check(lib().agg_kv_subsample(ctypes.byref(shape), _ptr(K), _ptr(V), _ptr(Kc), _ptr(Vc),
                                   _ptr(idx), _ptr(kmean), _ptr(vmean), _ptr(workspace),
                                   int(workspace_bytes), _stream(stream)), "agg_kv_subsample")
+
+
+def agg_static_scratch_bytes() -> int:
+    return int(lib().agg_static_scratch_bytes())
+
+
+def agg_kv_subsample_static(shape, K, V, Kc, Vc, idx, kmean, vmean, stream=None):
+    _check(lib().agg_kv_subsample_static(ctypes.byref(shape), _ptr(K), _ptr(V), _ptr(Kc), _ptr(Vc),
+                                         _ptr(idx), _ptr(kmean), _ptr(vmean), _stream(stream)),
+           "agg_kv_subsample_static")
 
 
 def agg_global_attn_fwd(shape, Q, K, V, Kc, Vc, kmean, vmean, O, lse=None, stream=None):

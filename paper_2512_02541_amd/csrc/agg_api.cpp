@@ -164,6 +164,26 @@ int agg_kv_subsample(const agg_shape* shape, const void* K, const void* V, void*
   return AGG_OK;
 }
 
+size_t agg_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int agg_kv_subsample_static(const agg_shape* shape, const void* K, const void* V, void* Kc,
+                            void* Vc, int32_t* idx, float* kmean, float* vmean, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (!K || !V || !Kc || !Vc || !kmean || !vmean) return AGG_ERR_NULL;
+  if (misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) || misaligned(kmean) ||
+      misaligned(vmean) || ((uintptr_t)idx & 3u))
+    return AGG_ERR_ALIGN;
+  if (agg_workspace_bytes(shape) > kStaticScratchBytes) return AGG_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if (static_scratch(&ws) != hipSuccess) return AGG_ERR_LAUNCH;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (launch_subsample(g, K, V, Kc, Vc, idx, kmean, vmean, ws, st) != hipSuccess)
+    return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
 int agg_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V,
                         const void* Kc, const void* Vc, const float* kmean, const float* vmean,
                         void* O, float* lse, void* hip_stream) {

@@ -6,6 +6,8 @@
 // that launch take one of two roles -- repack a 64-row tile of the compacted
 // set, or sum a run of dropped rows -- so that both kinds of traffic share the
 // memory system at the same time; a second, small launch adds the partial sums.
+#include <atomic>
+
 #include "agg_internal.h"
 
 namespace agg {
@@ -449,6 +451,34 @@ hipError_t launch_subsample(const Geom& g, const void* K, const void* V, void* K
                      (const float*)workspace, plan.nchunks, kmean, vmean, (const int32_t*)nullptr,
                      (int32_t*)nullptr);
   return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Scratch for callers that cannot allocate (agg_kv_subsample_static): the partial sums of the
+// mean live in a device array that is part of the library's code object.  In host code the
+// array's name is only a handle; its device address differs per GPU and is looked up once per
+// device (with that device current) and kept.  Nothing in it needs clearing: every partial that
+// the second stage reads is written by the first stage of the same call.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> scratch_ptr[kMaxDevices];
+
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    scratch_ptr[dev].store(p, std::memory_order_release);  // every thread finds the same address
+  }
+  *out = p;
+  return hipSuccess;
 }
 
 // Cell-mean variant: the compacted set holds, per window, the mean of its tokens.

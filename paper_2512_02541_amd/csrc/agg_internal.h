@@ -150,4 +150,9 @@ hipError_t launch_linear(const void* A, const LinearOuts& outs, const void* R, i
 
 int mean_chunks(const Geom& g);  // number of partial-sum blocks the mean kernel uses
 
+// Device array inside the library that stands in for the caller's workspace in
+// agg_kv_subsample_static; static_scratch() returns its address on the current device.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+hipError_t static_scratch(void** ptr);
+
 }  // namespace agg
