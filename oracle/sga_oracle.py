@@ -87,7 +87,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        # SGA_ORACLE_LIBRARY_PATH: another build of the same source (the sanitizer run of the tests)
+        _lib = ctypes.CDLL(os.environ.get("SGA_ORACLE_LIBRARY_PATH") or build())
         _lib.osga_num_threads.restype = ctypes.c_int
     return _lib
 

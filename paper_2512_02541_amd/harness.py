@@ -13,6 +13,42 @@ import torch
 from . import binding as agg
 
 
+# ---- guard regions ------------------------------------------------------------------------
+# With guards switched on (the GPU tests do), every buffer that a library call writes is
+# allocated with GUARD_BYTES of a fixed pattern behind it; check_all_guards() synchronises and
+# asserts that every pattern is intact: a bounds check on the kernels that cannot fault.
+GUARD_BYTES = 4096
+GUARD_VALUE = 0xA5
+guards_enabled = False
+_guards = []   # (name, raw uint8 tensor, payload bytes)
+
+
+def _buf(shape, dtype, device, name):
+    """torch.empty(shape, dtype) -- with a guard region behind it when guards are on."""
+    if not guards_enabled:
+        return torch.empty(shape, dtype=dtype, device=device)
+    shape = (shape,) if isinstance(shape, int) else tuple(shape)
+    numel = 1
+    for n in shape:
+        numel *= int(n)
+    nbytes = numel * torch.empty((), dtype=dtype).element_size()
+    raw = torch.empty(nbytes + GUARD_BYTES, dtype=torch.uint8, device=device)
+    raw[nbytes:].fill_(GUARD_VALUE)
+    _guards.append((name, raw, nbytes))
+    return raw[:nbytes].view(dtype).view(shape)
+
+
+def check_all_guards():
+    """Synchronises, asserts that no guard region was written, and forgets the buffers."""
+    if _guards:
+        torch.cuda.synchronize()
+    bad = [name for name, raw, n in _guards if not bool((raw[n:] == GUARD_VALUE).all())]
+    count = len(_guards)
+    _guards.clear()
+    assert not bad, "written past the end of: %s" % ", ".join(bad)
+    return count
+
+
 def shape_of(w, flags=agg.AGG_DIAG | agg.AGG_MEAN, s_h=None, s_w=None, keep_first_frame=None,
              mean_logit_bias=0.0, scale=None) -> agg.agg_shape:
     """agg_shape for a ``inputs.Workload`` (strides / first-frame rule overridable)."""
@@ -43,15 +79,14 @@ def alloc(shape: agg.agg_shape, device="cuda", with_lse=True, poison=False) -> S
     M, nd = agg.agg_kv_count(shape)
     nbytes, m_pad = agg.agg_kv_compact_bytes(shape)
     B, H, D, NQ = shape.B, shape.H, shape.D, shape.NQ
-    mk = torch.empty
-    Kc = mk(nbytes // 2, dtype=torch.bfloat16, device=device)
-    Vc = mk(nbytes // 2, dtype=torch.bfloat16, device=device)
-    idx = mk(M, dtype=torch.int32, device=device)
-    kmean = mk((B, H, D), dtype=torch.float32, device=device)
-    vmean = mk((B, H, D), dtype=torch.float32, device=device)
-    ws = mk(agg.agg_workspace_bytes(shape), dtype=torch.uint8, device=device)
-    O = mk((B, NQ, H, D), dtype=torch.bfloat16, device=device)
-    lse = mk((B, H, NQ), dtype=torch.float32, device=device) if with_lse else None
+    Kc = _buf(nbytes // 2, torch.bfloat16, device, "Kc")
+    Vc = _buf(nbytes // 2, torch.bfloat16, device, "Vc")
+    idx = _buf(M, torch.int32, device, "idx")
+    kmean = _buf((B, H, D), torch.float32, device, "kmean")
+    vmean = _buf((B, H, D), torch.float32, device, "vmean")
+    ws = _buf(agg.agg_workspace_bytes(shape), torch.uint8, device, "subsample workspace")
+    O = _buf((B, NQ, H, D), torch.bfloat16, device, "O")
+    lse = _buf((B, H, NQ), torch.float32, device, "lse") if with_lse else None
     if poison:  # make stale or unwritten memory visible to the comparison
         for t in (Kc, Vc, kmean, vmean, O):
             t.fill_(float("nan"))
@@ -82,10 +117,10 @@ def sga_forward(shape, Q, K, V, poison=False) -> SgaBuffers:
 
 def dense_forward(shape, Q, K, V, with_lse=True):
     B, H, D, NQ = shape.B, shape.H, shape.D, shape.NQ
-    O = torch.empty((B, NQ, H, D), dtype=torch.bfloat16, device=Q.device)
-    lse = torch.empty((B, H, NQ), dtype=torch.float32, device=Q.device) if with_lse else None
+    O = _buf((B, NQ, H, D), torch.bfloat16, Q.device, "dense O")
+    lse = _buf((B, H, NQ), torch.float32, Q.device, "dense lse") if with_lse else None
     nws = agg.agg_dense_workspace_bytes(shape)
-    ws = torch.empty(nws, dtype=torch.uint8, device=Q.device)
+    ws = _buf(nws, torch.uint8, Q.device, "dense workspace")
     agg.agg_dense_global_attn_fwd(shape, Q, K, V, O, lse, ws, nws)
     return O, lse
 
@@ -93,10 +128,10 @@ def dense_forward(shape, Q, K, V, with_lse=True):
 def frame_forward(shape, Q, K, V, with_lse=True):
     """Per-frame attention (Global-to-Frame conversion); lse comes back as [B*N, H, L]."""
     B, N, H, D, NQ = shape.B, shape.N, shape.H, shape.D, shape.NQ
-    O = torch.empty((B, NQ, H, D), dtype=torch.bfloat16, device=Q.device)
-    lse = torch.empty((B * N, H, shape.L), dtype=torch.float32, device=Q.device) if with_lse else None
+    O = _buf((B, NQ, H, D), torch.bfloat16, Q.device, "frame O")
+    lse = _buf((B * N, H, shape.L), torch.float32, Q.device, "frame lse") if with_lse else None
     nws = agg.agg_frame_workspace_bytes(shape)
-    ws = torch.empty(nws, dtype=torch.uint8, device=Q.device)
+    ws = _buf(nws, torch.uint8, Q.device, "frame workspace")
     agg.agg_frame_attn_fwd(shape, Q, K, V, O, lse, ws, nws)
     return O, lse
 
@@ -108,8 +143,8 @@ def block_forward(shape, mode, wts, x):
                                 wts["w_k"], wts["w_v"], wts["w_o"], wts.get("b_q"), wts.get("b_k"),
                                 wts.get("b_v"), wts.get("b_o"))
     nws = agg.agg_block_workspace_bytes(shape, mode)
-    ws = torch.empty(nws, dtype=torch.uint8, device=x.device)
-    y = torch.empty_like(x)
+    ws = _buf(nws, torch.uint8, x.device, "block workspace")
+    y = _buf(tuple(x.shape), x.dtype, x.device, "block y")
     agg.agg_global_block_fwd(shape, mode, cw, x, y, ws, nws)
     return y, ws
 
@@ -149,16 +184,15 @@ def list_forward(shape, kv_list, Q, K, V, poison=False) -> ListBuffers:
     M = kv_list.shape[1]
     nbytes, m_pad = agg.agg_list_compact_bytes(shape, M)
     dev = Q.device
-    mk = torch.empty
-    Kc = mk(nbytes // 2, dtype=torch.bfloat16, device=dev)
-    Vc = mk(nbytes // 2, dtype=torch.bfloat16, device=dev)
-    kmean = mk((B, H, D), dtype=torch.float32, device=dev)
-    vmean = mk((B, H, D), dtype=torch.float32, device=dev)
-    bits = mk((B, (NQ + 31) // 32), dtype=torch.int32, device=dev)
-    nd = mk((B,), dtype=torch.int32, device=dev)
-    ws = mk(agg.agg_list_workspace_bytes(shape), dtype=torch.uint8, device=dev)
-    O = mk((B, NQ, H, D), dtype=torch.bfloat16, device=dev)
-    lse = mk((B, H, NQ), dtype=torch.float32, device=dev)
+    Kc = _buf(nbytes // 2, torch.bfloat16, dev, "list Kc")
+    Vc = _buf(nbytes // 2, torch.bfloat16, dev, "list Vc")
+    kmean = _buf((B, H, D), torch.float32, dev, "list kmean")
+    vmean = _buf((B, H, D), torch.float32, dev, "list vmean")
+    bits = _buf((B, (NQ + 31) // 32), torch.int32, dev, "kept_bits")
+    nd = _buf((B,), torch.int32, dev, "n_dropped")
+    ws = _buf(agg.agg_list_workspace_bytes(shape), torch.uint8, dev, "list workspace")
+    O = _buf((B, NQ, H, D), torch.bfloat16, dev, "list O")
+    lse = _buf((B, H, NQ), torch.float32, dev, "list lse")
     if poison:
         for t in (Kc, Vc, kmean, vmean, O, lse):
             t.fill_(float("nan"))
@@ -173,7 +207,8 @@ def list_forward(shape, kv_list, Q, K, V, poison=False) -> ListBuffers:
 def select(shape, rule, seed, K):
     """Device int32 [B, M] list chosen by `rule` (agg_select_kv_indices)."""
     M, _ = agg.agg_kv_count(shape)
-    out = torch.full((shape.B, M), -1, dtype=torch.int32, device=K.device)
+    out = _buf((shape.B, M), torch.int32, K.device, "selected list")
+    out.fill_(-1)
     agg.agg_select_kv_indices(shape, rule, seed, K, out)
     return out
 

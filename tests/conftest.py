@@ -21,3 +21,22 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _guard_regions(request):
+    """GPU tests allocate every buffer the library writes with a patterned guard region behind
+    it (harness._buf); after the test all of them must be intact."""
+    if request.node.get_closest_marker("gpu") is None:
+        yield
+        return
+    from paper_2512_02541_amd import harness
+
+    harness.guards_enabled = True
+    harness._guards.clear()
+    try:
+        yield
+        harness.check_all_guards()
+    finally:
+        harness.guards_enabled = False
+        harness._guards.clear()

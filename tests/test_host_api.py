@@ -242,3 +242,31 @@ def test_product_and_oracle_share_nothing():
     for m in re.finditer(r"^\s*(from|import)\s+oracle\b.*$", bench, flags=re.M):
         last_def = re.findall(r"^def (\w+)\(", bench[:m.start()], flags=re.M)[-1]
         assert last_def == "cpu_baseline", (m.group(0), last_def)
+
+
+def test_attention_kernel_leaves_m0_to_its_copy_statements(tmp_path):
+    """The attention kernel's global->LDS copies set the M0 register inside assembly statements
+    without declaring it (the compiler rejects M0 as a clobber).  That is sound only while no
+    compiler-emitted instruction of those kernels uses M0: compile the file to assembly and
+    look at every instruction outside the statements."""
+    import subprocess
+
+    from paper_2512_02541_amd import build as b
+
+    out = tmp_path / "agg_attn.s"
+    cmd = [b.HIPCC, *b.FLAGS, "-I", os.path.join(ROOT, "include"), "-I", b.CSRC, "-S",
+           "--cuda-device-only", os.path.join(b.CSRC, "agg_attn.hip"), "-o", str(out)]
+    subprocess.check_call(cmd, stderr=subprocess.DEVNULL)
+    inside, seen_copy, offenders = False, 0, []
+    for line in out.read_text().splitlines():
+        text = line.split(";")[0] if not line.lstrip().startswith(";;#") else line
+        if "#ASMSTART" in line:
+            inside = True
+        elif "#ASMEND" in line:
+            inside = False
+        elif inside:
+            seen_copy += "global_load_lds_dwordx4" in text
+        elif re.search(r"\bm0\b", text):
+            offenders.append(line.strip())
+    assert seen_copy >= 4, "the copy statements were not found"
+    assert not offenders, offenders[:5]
