@@ -94,28 +94,29 @@ def run_workload(name, steps, warmup, dense, log):
         "gather_frac_hbm": gather_bytes / (ms_gather * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "flops_per_layer": flops, "gather_bytes": gather_bytes,
     }
+    # the same layer with the kernel reading the kept rows in place through the index list
+    Oi = torch.empty_like(buf.O)
+    ms_idx, _ = time_events(lambda: agg.agg_global_attn_fwd_idx(
+        shape, q, k, v, buf.idx, buf.kmean, buf.vmean, Oi, None), max(2, min(steps, 3)), 1)
+    res.update({"ms_attn_idx": ms_idx, "tflops_attn_idx": flops / (ms_idx * 1e-3) / 1e12})
+    del Oi
     if dense:
-        nws = agg.agg_dense_workspace_bytes(shape)
-        ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
         Od = torch.empty_like(buf.O)
 
         def dense_step():
-            agg.agg_dense_global_attn_fwd(shape, q, k, v, Od, None, ws, nws)
+            agg.agg_dense_global_attn_fwd(shape, q, k, v, Od, None)
 
         ms_dense, _ = time_events(dense_step, max(1, min(steps, 3)), 1)
         dflops = 4.0 * w.NQ * w.NQ * w.D * w.H
         res.update({"ms_dense": ms_dense, "tflops_dense": dflops / (ms_dense * 1e-3) / 1e12,
                     "speedup_vs_dense": ms_dense / ms_step,
                     "ideal_speedup": w.NQ / buf.M})
-        del ws
         # frame attention (Global-to-Frame conversion of an early global block), same tensors
-        nwf = agg.agg_frame_workspace_bytes(shape)
-        wf = torch.empty(nwf, dtype=torch.uint8, device="cuda")
         ms_frame, _ = time_events(
-            lambda: agg.agg_frame_attn_fwd(shape, q, k, v, Od, None, wf, nwf), max(1, min(steps, 3)), 1)
+            lambda: agg.agg_frame_attn_fwd(shape, q, k, v, Od, None), max(1, min(steps, 3)), 1)
         fflops = 4.0 * w.N * w.L * w.L * w.D * w.H
         res.update({"ms_frame_attn": ms_frame, "tflops_frame_attn": fflops / (ms_frame * 1e-3) / 1e12})
-        del wf, Od
+        del Od
     return res, (w, shape, q, k, v, buf)
 
 
@@ -210,16 +211,13 @@ def run_only(args, log):
                           "tflops_attn": fl / (ms * 1e-3) / 1e12,
                           "frac_peak": fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}))
         return 0
-    if args.only == "dense":
-        nws = agg.agg_dense_workspace_bytes(shape)
-        ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
     for _ in range(args.steps):
         if args.only == "attn":
             harness.attend(buf, q, k, v)
         elif args.only == "gather":
             harness.subsample(buf, k, v)
         else:
-            agg.agg_dense_global_attn_fwd(shape, q, k, v, buf.O, None, ws, nws)
+            agg.agg_dense_global_attn_fwd(shape, q, k, v, buf.O, None)
     torch.cuda.synchronize()
     print(json.dumps({"only": args.only, "workload": args.workload, "launches": args.steps,
                       "flops_per_launch": sga_flops(w.NQ, buf.M, w.H, w.D),
@@ -441,7 +439,7 @@ def main():
         torch.cuda.empty_cache()
         also.append({k: r[k] for k in ("workload", "frames", "NQ", "M", "strides", "ms_layer",
                                        "ms_gather", "ms_attn", "tflops_attn", "frac_peak_attn",
-                                       "gather_gbs")})
+                                       "gather_gbs", "ms_attn_idx")})
 
     out = {
         "metric": METRIC,
@@ -460,6 +458,8 @@ def main():
                    "ms_dense": res.get("ms_dense"), "tflops_dense": res.get("tflops_dense"),
                    "ms_frame_attn": res.get("ms_frame_attn"),
                    "tflops_frame_attn": res.get("tflops_frame_attn"),
+                   "ms_attn_idx": res.get("ms_attn_idx"),
+                   "tflops_attn_idx": res.get("tflops_attn_idx"),
                    "speedup_vs_dense": res.get("speedup_vs_dense"),
                    "ideal_speedup": res.get("ideal_speedup"),
                    "paper_context": "end-to-end speedups ~2x/4-5x/8-10x at 100/300/800 frames on "

@@ -99,9 +99,6 @@ int64_t agg_vc_offset(int64_t m, int32_t d);
 /* Host only.  Scratch bytes agg_kv_subsample needs (partial sums of the mean). */
 size_t agg_workspace_bytes(const agg_shape* shape);
 
-/* Host only.  Scratch bytes agg_dense_global_attn_fwd needs (K and V in fragment order). */
-size_t agg_dense_workspace_bytes(const agg_shape* shape);
-
 /*
  * Sec. 4.3, subsampling + mean component.  Builds on the device:
  *   idx   [M] int32        ascending kept token ids (same for every batch element/head/layer)
@@ -110,7 +107,9 @@ size_t agg_dense_workspace_bytes(const agg_shape* shape);
  *         sequence (zeros when nothing is dropped).  Accumulated in a fixed order:
  *         results are bit-reproducible run to run.
  * K, V: device bf16 [B, N*L, H, D].  workspace: device, >= agg_workspace_bytes().
- * idx may be NULL (not written).  kmean/vmean must be non-NULL.
+ * idx may be NULL (not written).  kmean/vmean must be non-NULL.  Kc and Vc may BOTH be NULL:
+ * then no compacted copy is made and only idx and the mean terms are produced, which is all
+ * that agg_global_attn_fwd_idx needs.
  */
 int agg_kv_subsample(const agg_shape* shape, const void* K, const void* V, void* Kc, void* Vc,
                      int32_t* idx, float* kmean, float* vmean, void* workspace,
@@ -149,26 +148,34 @@ int agg_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, co
                         void* O, float* lse, void* hip_stream);
 
 /*
+ * Sec. 4.3 again, without a compacted copy: the same attention as agg_global_attn_fwd, with the
+ * kernel fetching the kept rows of K and V in place through idx (the paper's statement is just
+ * that: only a subset of the tokens serves as keys and values).  idx: device int32 [M], the
+ * ascending kept token ids as agg_kv_subsample writes them; kmean, vmean: as above.  Results are
+ * bit-identical to agg_global_attn_fwd.  Needs N*L < 2^24 and N*L*H*D*2 < 2^32 (rows are
+ * addressed with 32-bit offsets inside one batch element's head); otherwise AGG_ERR_OVERFLOW.
+ */
+int agg_global_attn_fwd_idx(const agg_shape* shape, const void* Q, const void* K, const void* V,
+                            const int32_t* idx, const float* kmean, const float* vmean, void* O,
+                            float* lse, void* hip_stream);
+
+/*
  * Sec. 4.2: ordinary global attention over the (B, N*L, C) layout -- every token of the
  * sequence is a key -- the s = 1 baseline SGA is measured against.  shape->s_h, s_w,
- * flags and keep_first_frame are ignored.  workspace: device, >= agg_dense_workspace_bytes();
- * it receives K and V repacked into fragment order and can be discarded after the call's
- * work has finished.
+ * flags and keep_first_frame are ignored.  K and V are read in place (no copy, no workspace).
  */
 int agg_dense_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V,
-                              void* O, float* lse, void* workspace, size_t workspace_bytes,
-                              void* hip_stream);
+                              void* O, float* lse, void* hip_stream);
 
 /*
  * Sec. 4.2, Global-to-Frame conversion: attention applied independently inside every frame,
  * i.e. on the (B*N, L, C) layout -- what an early global block becomes when its rearrangement
  * to (B, N*L, C) is skipped.  Q, K, V, O: the same device tensors as above (a frame's tokens are
  * contiguous in them).  lse: device float32 [B*N, H, L] or NULL.  shape->s_h, s_w, flags and
- * keep_first_frame are ignored.  workspace: device, >= agg_frame_workspace_bytes().
+ * keep_first_frame are ignored.
  */
-size_t agg_frame_workspace_bytes(const agg_shape* shape);
 int agg_frame_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V, void* O,
-                       float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+                       float* lse, void* hip_stream);
 
 /*
  * One global-attention block around the calls above (Sec. 4.2: a converted or subsampled

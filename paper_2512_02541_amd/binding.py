@@ -61,8 +61,8 @@ _lib = None
 EXPORTS = [
     "agg_status_string", "agg_sigma_to_strides", "agg_kv_count", "agg_kv_indices_host",
     "agg_dropped_indices_host", "agg_kv_compact_bytes", "agg_kc_offset", "agg_vc_offset", "agg_workspace_bytes",
-    "agg_dense_workspace_bytes", "agg_kv_subsample", "agg_global_attn_fwd",
-    "agg_dense_global_attn_fwd", "agg_frame_workspace_bytes", "agg_frame_attn_fwd",
+    "agg_kv_subsample", "agg_global_attn_fwd", "agg_global_attn_fwd_idx",
+    "agg_dense_global_attn_fwd", "agg_frame_attn_fwd",
     "agg_block_workspace_bytes", "agg_global_block_fwd",
     "agg_select_kv_indices", "agg_list_compact_bytes", "agg_list_workspace_bytes",
     "agg_kv_subsample_list", "agg_global_attn_fwd_list", "agg_kv_pool",
@@ -127,14 +127,11 @@ def lib():
     L.agg_vc_offset.argtypes = [ctypes.c_int64, ctypes.c_int32]
     L.agg_workspace_bytes.restype = ctypes.c_size_t
     L.agg_workspace_bytes.argtypes = [shp]
-    L.agg_dense_workspace_bytes.restype = ctypes.c_size_t
-    L.agg_dense_workspace_bytes.argtypes = [shp]
     L.agg_kv_subsample.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.agg_global_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
-    L.agg_dense_global_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
-    L.agg_frame_workspace_bytes.restype = ctypes.c_size_t
-    L.agg_frame_workspace_bytes.argtypes = [shp]
-    L.agg_frame_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.agg_global_attn_fwd_idx.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.agg_dense_global_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+    L.agg_frame_attn_fwd.argtypes = [shp, vp, vp, vp, vp, vp, vp]
     L.agg_block_workspace_bytes.restype = ctypes.c_size_t
     L.agg_block_workspace_bytes.argtypes = [shp, ctypes.c_int]
     L.agg_global_block_fwd.argtypes = [shp, ctypes.c_int, ctypes.POINTER(agg_block_weights), vp, vp,
@@ -235,10 +232,6 @@ def agg_workspace_bytes(shape: agg_shape) -> int:
     return int(lib().agg_workspace_bytes(ctypes.byref(shape)))
 
 
-def agg_dense_workspace_bytes(shape: agg_shape) -> int:
-    return int(lib().agg_dense_workspace_bytes(ctypes.byref(shape)))
-
-
 def agg_kv_subsample(shape, K, V, Kc, Vc, idx, kmean, vmean, workspace, workspace_bytes,
                      stream=None):
     _check(lib().agg_kv_subsample(ctypes.byref(shape), _ptr(K), _ptr(V), _ptr(Kc), _ptr(Vc),
@@ -262,20 +255,20 @@ def agg_global_attn_fwd(shape, Q, K, V, Kc, Vc, kmean, vmean, O, lse=None, strea
                                      _stream(stream)), "agg_global_attn_fwd")
 
 
-def agg_dense_global_attn_fwd(shape, Q, K, V, O, lse, workspace, workspace_bytes, stream=None):
+def agg_global_attn_fwd_idx(shape, Q, K, V, idx, kmean, vmean, O, lse=None, stream=None):
+    _check(lib().agg_global_attn_fwd_idx(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx),
+                                         _ptr(kmean), _ptr(vmean), _ptr(O), _ptr(lse),
+                                         _stream(stream)), "agg_global_attn_fwd_idx")
+
+
+def agg_dense_global_attn_fwd(shape, Q, K, V, O, lse=None, stream=None):
     _check(lib().agg_dense_global_attn_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
-                                           _ptr(lse), _ptr(workspace), int(workspace_bytes),
-                                           _stream(stream)), "agg_dense_global_attn_fwd")
+                                           _ptr(lse), _stream(stream)), "agg_dense_global_attn_fwd")
 
 
-def agg_frame_workspace_bytes(shape: agg_shape) -> int:
-    return int(lib().agg_frame_workspace_bytes(ctypes.byref(shape)))
-
-
-def agg_frame_attn_fwd(shape, Q, K, V, O, lse, workspace, workspace_bytes, stream=None):
+def agg_frame_attn_fwd(shape, Q, K, V, O, lse=None, stream=None):
     _check(lib().agg_frame_attn_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
-                                    _ptr(lse), _ptr(workspace), int(workspace_bytes),
-                                    _stream(stream)), "agg_frame_attn_fwd")
+                                    _ptr(lse), _stream(stream)), "agg_frame_attn_fwd")
 
 
 def agg_block_workspace_bytes(shape: agg_shape, mode: int) -> int:

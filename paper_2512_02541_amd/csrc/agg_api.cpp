@@ -141,19 +141,14 @@ size_t agg_workspace_bytes(const agg_shape* shape) {
   return n ? n : 256;
 }
 
-size_t agg_dense_workspace_bytes(const agg_shape* shape) {
-  Geom g;
-  if (make_geom(shape, &g, true) != AGG_OK) return 0;
-  return 2 * (size_t)g.B * g.H * g.M_pad * kHeadDim * 2;
-}
-
 int agg_kv_subsample(const agg_shape* shape, const void* K, const void* V, void* Kc, void* Vc,
                      int32_t* idx, float* kmean, float* vmean, void* workspace,
                      size_t workspace_bytes, void* hip_stream) {
   Geom g;
   int rc = make_geom(shape, &g, false);
   if (rc != AGG_OK) return rc;
-  if (!K || !V || !Kc || !Vc || !kmean || !vmean || !workspace) return AGG_ERR_NULL;
+  if (!K || !V || !kmean || !vmean || !workspace) return AGG_ERR_NULL;
+  if ((Kc == nullptr) != (Vc == nullptr)) return AGG_ERR_NULL;  // both or neither
   if (misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) || misaligned(workspace) ||
       misaligned(kmean) || misaligned(vmean) || ((uintptr_t)idx & 3u))
     return AGG_ERR_ALIGN;
@@ -201,26 +196,42 @@ int agg_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, co
   return AGG_OK;
 }
 
+// Whether the in-place row modes of the attention kernel can address this geometry: indexed
+// rows use 32-bit byte offsets from the (batch, head) base formed by a 24-bit multiplication.
+static bool rows_addressable(const Geom& g) {
+  return (uint64_t)g.NQ * g.H * (kHeadDim * 2) <= 0xFFFFFFFFull && g.NQ <= 0xFFFFFF &&
+         (uint64_t)g.H * (kHeadDim * 2) <= 0xFFFFFF;
+}
+
+int agg_global_attn_fwd_idx(const agg_shape* shape, const void* Q, const void* K, const void* V,
+                            const int32_t* idx, const float* kmean, const float* vmean, void* O,
+                            float* lse, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(shape, &g, false);
+  if (rc != AGG_OK) return rc;
+  if (!Q || !K || !V || !idx || !kmean || !vmean || !O) return AGG_ERR_NULL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(kmean) ||
+      misaligned(vmean) || ((uintptr_t)idx & 3u) || ((uintptr_t)lse & 3u))
+    return AGG_ERR_ALIGN;
+  if (!rows_addressable(g)) return AGG_ERR_OVERFLOW;
+  if (launch_attn(g, shape->flags, shape->scale, shape->mean_logit_bias, Q, K, V, nullptr, nullptr,
+                  kmean, vmean, O, lse, (hipStream_t)hip_stream, nullptr, nullptr, kAttnSrcIndexed,
+                  idx, 0) != hipSuccess)
+    return AGG_ERR_LAUNCH;
+  return AGG_OK;
+}
+
 int agg_dense_global_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V,
-                              void* O, float* lse, void* workspace, size_t workspace_bytes,
-                              void* hip_stream) {
+                              void* O, float* lse, void* hip_stream) {
   Geom g;
   int rc = make_geom(shape, &g, true);
   if (rc != AGG_OK) return rc;
-  if (!Q || !K || !V || !O || !workspace) return AGG_ERR_NULL;
-  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(workspace) ||
-      ((uintptr_t)lse & 3u))
+  if (!Q || !K || !V || !O) return AGG_ERR_NULL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || ((uintptr_t)lse & 3u))
     return AGG_ERR_ALIGN;
-  if (workspace_bytes < agg_dense_workspace_bytes(shape)) return AGG_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)hip_stream;
-  size_t one = (size_t)g.B * g.H * g.M_pad * kHeadDim * 2;
-  void* Kf = workspace;
-  void* Vf = (char*)workspace + one;
-  // repack every row (nothing dropped), then the same attention kernel with no extras
-  if (launch_subsample(g, K, V, Kf, Vf, nullptr, nullptr, nullptr, nullptr, st) != hipSuccess)
-    return AGG_ERR_LAUNCH;
-  if (launch_attn(g, 0u, shape->scale, 0.0f, Q, K, V, Kf, Vf, nullptr, nullptr, O, lse, st) !=
-      hipSuccess)
+  // every token is a key: the kernel reads the rows of K and V where they are, no extras
+  if (launch_attn(g, 0u, shape->scale, 0.0f, Q, K, V, nullptr, nullptr, nullptr, nullptr, O, lse,
+                  (hipStream_t)hip_stream, nullptr, nullptr, kAttnSrcRows) != hipSuccess)
     return AGG_ERR_LAUNCH;
   return AGG_OK;
 }
@@ -237,18 +248,12 @@ static int frame_shape(const agg_shape* shape, agg_shape* per_frame) {
   return AGG_OK;
 }
 
-size_t agg_frame_workspace_bytes(const agg_shape* shape) {
-  agg_shape f;
-  if (frame_shape(shape, &f) != AGG_OK) return 0;
-  return agg_dense_workspace_bytes(&f);
-}
-
 int agg_frame_attn_fwd(const agg_shape* shape, const void* Q, const void* K, const void* V, void* O,
-                       float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                       float* lse, void* hip_stream) {
   agg_shape f;
   int rc = frame_shape(shape, &f);
   if (rc != AGG_OK) return rc;
-  return agg_dense_global_attn_fwd(&f, Q, K, V, O, lse, workspace, workspace_bytes, hip_stream);
+  return agg_dense_global_attn_fwd(&f, Q, K, V, O, lse, hip_stream);
 }
 
 // ---- caller-supplied kept lists ---------------------------------------------------------
@@ -370,10 +375,8 @@ int plan_block(const agg_shape* shape, int mode, BlockPlan* p) {
     p->compact = align256((size_t)g.B * g.H * g.M_pad * kHeadDim * 2);
     const size_t means = align256((size_t)g.B * g.H * kHeadDim * sizeof(float));
     p->attn_ws = 2 * p->compact + 2 * means + align256(agg_workspace_bytes(shape));
-  } else if (mode == AGG_BLOCK_FRAME) {
-    p->attn_ws = align256(agg_frame_workspace_bytes(shape));
   } else {
-    p->attn_ws = align256(agg_dense_workspace_bytes(shape));
+    p->attn_ws = 0;  // per-frame and ordinary attention read K and V in place
   }
   p->total = 5 * p->act + p->attn_ws;
   return AGG_OK;
@@ -434,9 +437,9 @@ int agg_global_block_fwd(const agg_shape* shape, int mode, const agg_block_weigh
     if (rc != AGG_OK) return rc;
     rc = agg_global_attn_fwd(shape, Q, K, V, Kc, Vc, kmean, vmean, A, nullptr, hip_stream);
   } else if (mode == AGG_BLOCK_FRAME) {
-    rc = agg_frame_attn_fwd(shape, Q, K, V, A, nullptr, aws, p.attn_ws, hip_stream);
+    rc = agg_frame_attn_fwd(shape, Q, K, V, A, nullptr, hip_stream);
   } else {
-    rc = agg_dense_global_attn_fwd(shape, Q, K, V, A, nullptr, aws, p.attn_ws, hip_stream);
+    rc = agg_dense_global_attn_fwd(shape, Q, K, V, A, nullptr, hip_stream);
   }
   if (rc != AGG_OK) return rc;
   const LinearOuts out = {{(const uint16_t*)w->w_o, nullptr, nullptr},

@@ -178,25 +178,204 @@ struct Wave {
   Frag P[2];           // probabilities of the previous unit
 };
 
+// Where the key/value tiles come from.
+//   kSrcCompact: the fragment-order compacted tensors of agg_kv_subsample: a tile is a linear
+//                8 KiB copy and already in MFMA operand order.
+//   kSrcRows:    consecutive rows of the token-major K and V themselves (ordinary and per-frame
+//                attention: every token is a key), no compacted copy.
+//   kSrcIndexed: rows of K and V picked through a list of token ids (Sec. 4.3 restricts keys
+//                and values to a subset of the tokens; here the subset is read in place).
+// In the two row modes a tile lies in LDS row-major, 128 bytes per key, with the 16-byte chunk
+// number XOR-ed by a function of the row so that the fragment reads spread over all 64 banks:
+// K fragments (eight channels of one key per lane) are plain 16-byte reads; V fragments (eight
+// keys of one channel per lane) come from the transposing read ds_read_b64_tr_b16, which hands
+// lane i of a 16-lane group the i-th 16-bit column of the four 8-byte rows the group's lanes
+// 4j .. 4j+3 point at.
+enum { kSrcCompact = 0, kSrcRows = 1, kSrcIndexed = 2 };
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) char lds_char;
+
+// per-lane LDS byte offsets of the fragment reads (row modes) or chunk numbers (compact mode)
+struct FragAddr {
+  int lane, vlane;       // compact: chunk numbers inside a K / V tile
+  uint32_t k[4];         // rows: K fragment of channel step ks (chunk swizzle depends on the lane)
+  uint32_t v[2];         // rows: V fragment of channel block db
+};
+
+__device__ __forceinline__ FragAddr frag_addr(int lane) {
+  FragAddr f;
+  const int l32 = lane & 31, g2 = lane >> 5;
+  f.lane = lane;
+  f.vlane = g2 * 64 + l32;
+  // K, row l32 of a 32-key block: chunk (2 ks + g2) ^ ((row >> 1) & 7), row parity picks the
+  // half of the 256-byte bank period
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    f.k[ks] = (uint32_t)(l32 * 128 + (((2 * ks + g2) ^ ((l32 >> 1) & 7)) * 16));
+  // V: lane i of a 16-lane group reads row 4 g2 + i/4 (+ the block's first row), the 8 bytes at
+  // channel 32 db + 16 (group & 1) + 4 (i % 4); chunk bit 2 is flipped on rows 2, 3 mod 4
+  const int i = lane & 15, grp = (lane >> 4) & 1;
+  const int row = 4 * g2 + (i >> 2);
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+    const int chunk = (4 * db + 2 * grp + ((i & 3) >> 1)) ^ (4 * ((row >> 1) & 1));
+    f.v[db] = (uint32_t)(row * 128 + chunk * 16 + (i & 1) * 8);
+  }
+  return f;
+}
+
+template <int kSrc>
 __device__ __forceinline__ void load_k_frags(const u32x4* __restrict__ lds, int buf, int kb,
-                                             int lane, Frag (&a)[4]) {
+                                             const FragAddr& f, Frag (&a)[4]) {
+  if (kSrc == kSrcCompact) {
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) a[ks].u = lds[buf * kChunks + (kb * 4 + ks) * 64 + lane];
+    for (int ks = 0; ks < 4; ++ks) a[ks].u = lds[buf * kChunks + (kb * 4 + ks) * 64 + f.lane];
+  } else {
+    const lds_char* base = (const lds_char*)lds + buf * (kChunks * 16) + kb * (32 * 128);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      a[ks].u = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(base + f.k[ks]);
+  }
 }
+template <int kSrc>
 __device__ __forceinline__ void load_v_frags(const u32x4* __restrict__ lds, int buf, int kb,
-                                             int vlane, Frag (&v)[4]) {
+                                             const FragAddr& f, Frag (&v)[4]) {
+  if (kSrc == kSrcCompact) {
 #pragma unroll
-  for (int hf = 0; hf < 2; ++hf)
+    for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
-      v[hf * 2 + db].u = lds[(kLdsTiles + buf) * kChunks + (kb * 2 + hf) * 128 + db * 32 + vlane];
+      for (int db = 0; db < 2; ++db)
+        v[hf * 2 + db].u =
+            lds[(kLdsTiles + buf) * kChunks + (kb * 2 + hf) * 128 + db * 32 + f.vlane];
+  } else {
+    lds_char* base = (lds_char*)lds + (kLdsTiles + buf) * (kChunks * 16) + kb * (32 * 128);
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        // keys 16 hf + 4 g2 + 0..3, then 16 hf + 8 + 4 g2 + 0..3: the order the P operand has
+        lds_char* at = base + hf * (16 * 128) + f.v[db];
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)at);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(at + 8 * 128));
+        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+        v[hf * 2 + db].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
+      }
+  }
 }
+
+// What a workgroup needs to know about its key/value source.
+struct KvSource {
+  const uint16_t *k, *v;   // compact: tile 0 of this (batch, head); rows: token 0's row of this head
+  const int32_t* list;     // indexed: the batch element's token ids
+  int64_t rows;            // number of keys (M, or the sequence length)
+  uint32_t row_bytes;      // rows: distance between consecutive tokens' rows (H * 128)
+  uint32_t max_token;      // indexed: largest valid token id (N*L - 1)
+};
+
+// Issues the asynchronous copy of tile t into LDS buffer `buf`.  Every wavefront lands 64
+// consecutive 16-byte LDS slots per instruction; which global chunk a lane fetches for its slot
+// is what differs between the modes.
+template <int kSrc>
+struct TileCopier {
+  KvSource src;
+  const uint16_t *knext, *vnext;  // compact, rows: where the next tile to be copied starts
+  int64_t tnext;                  // its number (tiles are copied in order)
+  uint32_t wbase;          // LDS byte address of this wavefront's first slot in buffer 0
+  uint32_t vk[2], vv[2];   // byte offset of this lane's two chunks from the tile's (rows, compact)
+                           // or the row's (indexed) start, for K and for V
+  uint32_t row[2];         // row of the tile this lane's slots belong to (row modes)
+  int32_t tok[2];          // indexed: token ids of those rows for the next tile to be copied
+
+  __device__ __forceinline__ void init(const KvSource& s, const u32x4* lds, int tid, int wave) {
+    src = s;
+    knext = s.k;
+    vnext = s.v;
+    tnext = 0;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)lds);
+    wbase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)wave * 1024u);
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const uint32_t slot = (uint32_t)tid + hh * kAttnThreads;  // 0 .. 511
+      row[hh] = slot >> 3;
+      const uint32_t c = slot & 7;
+      const uint32_t ck = (c ^ ((row[hh] >> 1) & 7)) * 16u;
+      const uint32_t cv = (c ^ (4u * ((row[hh] >> 1) & 1))) * 16u;
+      if (kSrc == kSrcCompact) {
+        vk[hh] = vv[hh] = slot * 16u;
+      } else if (kSrc == kSrcRows) {
+        vk[hh] = row[hh] * s.row_bytes + ck;
+        vv[hh] = row[hh] * s.row_bytes + cv;
+      } else {
+        vk[hh] = ck;
+        vv[hh] = cv;
+      }
+      tok[hh] = 0;
+    }
+    if (kSrc == kSrcIndexed) fetch_tokens(0);
+  }
+  __device__ __forceinline__ void fetch_tokens(int64_t t) {  // indexed: ids of tile t's rows
+    const uint32_t m0 = (uint32_t)t * kTileRows, last = (uint32_t)src.rows - 1u;
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {  // rows past the end repeat the last one; masked later
+      const uint32_t id = (uint32_t)src.list[min(m0 + row[hh], last)];
+      tok[hh] = (int32_t)min(id, src.max_token);  // an id outside the sequence cannot leave it
+    }
+  }
+  // copies tile tnext into LDS buffer `buf`
+  __device__ __forceinline__ void issue(int buf) {
+    const uint32_t mk = wbase + (uint32_t)buf * (kChunks * 16);
+    const uint32_t mv = wbase + (uint32_t)(kLdsTiles + buf) * (kChunks * 16);
+    constexpr int kInstr = kAttnThreads < kChunks ? 2 : 1;
+    if (kSrc == kSrcCompact) {
+#pragma unroll
+      for (int hh = 0; hh < kInstr; ++hh) {
+        dma16(knext, vk[hh], mk + hh * kAttnThreads * 16);
+        dma16(vnext, vv[hh], mv + hh * kAttnThreads * 16);
+      }
+      knext += kTileElems;
+      vnext += kTileElems;
+    } else if (kSrc == kSrcRows) {
+      // the tile's rows follow each other in memory
+      if ((tnext + 1) * kTileRows <= src.rows) {
+#pragma unroll
+        for (int hh = 0; hh < kInstr; ++hh) {
+          dma16(knext, vk[hh], mk + hh * kAttnThreads * 16);
+          dma16(vnext, vv[hh], mv + hh * kAttnThreads * 16);
+        }
+      } else {  // last, partial tile: rows past the end repeat the last one; masked later
+        const uint32_t last = (uint32_t)(src.rows - 1 - tnext * kTileRows);
+#pragma unroll
+        for (int hh = 0; hh < kInstr; ++hh) {
+          const uint32_t back = row[hh] > last ? (row[hh] - last) * src.row_bytes : 0u;
+          dma16(knext, vk[hh] - back, mk + hh * kAttnThreads * 16);
+          dma16(vnext, vv[hh] - back, mv + hh * kAttnThreads * 16);
+        }
+      }
+      knext += (size_t)kTileRows * (src.row_bytes / 2);
+      vnext += (size_t)kTileRows * (src.row_bytes / 2);
+    } else {
+      // token ids were fetched a tile ahead; the next tile's are fetched once these are used
+#pragma unroll
+      for (int hh = 0; hh < kInstr; ++hh) {
+        const uint32_t base = __umul24((uint32_t)tok[hh], src.row_bytes);
+        dma16(src.k, base + vk[hh], mk + hh * kAttnThreads * 16);
+        dma16(src.v, base + vv[hh], mv + hh * kAttnThreads * 16);
+      }
+      fetch_tokens(tnext + 1);
+    }
+    ++tnext;
+  }
+};
 
 // One step of the pipeline inside tile `cur` (see the file header).  kLast: the tile is the
 // last one (`valid` of its 64 rows exist, nothing follows).  kGen: general path.
-template <bool kLast, bool kGen>
+template <int kSrc, bool kLast, bool kGen>
 __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ lds, int cur, int nxt,
-                                           int valid, int lane, int vlane, int g2) {
+                                           int valid, const FragAddr& fa, int g2) {
+  const int lane = fa.lane;
 #pragma unroll
   for (int sg = 0; sg < 2 * kQB; ++sg) {
     const int kb = sg / kQB, qb = sg % kQB;
@@ -217,8 +396,8 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
       for (int ks = 1; ks < 4; ++ks) Sn = AGG_MFMA(w.a[ks], w.Qf[tq][ks], Sn);
     }
     if (tq == kQB - 1) {  // that was the block's last unit: fragments of the following block
-      if (un / kQB == 0) load_k_frags(lds, cur, 1, lane, w.a);
-      else if (!kLast) load_k_frags(lds, nxt, 0, lane, w.a);
+      if (un / kQB == 0) load_k_frags<kSrc>(lds, cur, 1, fa, w.a);
+      else if (!kLast) load_k_frags<kSrc>(lds, nxt, 0, fa, w.a);
     }
 
     // ---- vector ALU: probabilities of unit sg ----
@@ -242,12 +421,10 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
           f32x16 R;
 #pragma unroll
           for (int r = 0; r < 16; ++r) R[r] = 0.f;
+          Frag kf[4];
+          load_k_frags<kSrc>(lds, cur, kb, fa, kf);
 #pragma unroll
-          for (int ks = 0; ks < 4; ++ks) {
-            Frag kf;
-            kf.u = lds[cur * kChunks + (kb * 4 + ks) * 64 + lane];
-            R = AGG_MFMA(kf, w.Qf[qb][ks], R);
-          }
+          for (int ks = 0; ks < 4; ++ks) R = AGG_MFMA(kf[ks], w.Qf[qb][ks], R);
           if (kLast && valid < kTileRows) mask16(R, kb, valid, g2);
           float mx = R[0];
 #pragma unroll
@@ -279,7 +456,7 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
     w.O[pq][1] = AGG_MFMA(w.v[1], w.P[0], w.O[pq][1]);
     w.O[pq][0] = AGG_MFMA(w.v[2], w.P[1], w.O[pq][0]);
     w.O[pq][1] = AGG_MFMA(w.v[3], w.P[1], w.O[pq][1]);
-    if (qb == 0) load_v_frags(lds, cur, kb, vlane, w.v);  // the previous block is done with them
+    if (qb == 0) load_v_frags<kSrc>(lds, cur, kb, fa, w.v);  // the previous block is done with them
     w.P[0] = Pn[0];
     w.P[1] = Pn[1];
     // Issue order inside the step: one MFMA, then its share of the vector work (two
@@ -295,32 +472,23 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
   }
 }
 
-// The key loop of one path.  Returns false when the fast path found a row sum it cannot trust.
-template <bool kGen>
-__device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const uint16_t* kc,
-                                         const uint16_t* vc, int ntiles, int last_valid, int tid,
-                                         int wave, int lane, int vlane, int g2) {
-  // this wavefront's share of a tile copy: 64 consecutive chunks per instruction
-  const uint32_t voff0 = (uint32_t)tid * 16u;
-  const uint32_t voff1 = voff0 + (uint32_t)kAttnThreads * 16u;
-  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
-  const uint32_t wbase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)wave * 1024u);
-  auto copy_tile = [&](const uint16_t* ksrc, const uint16_t* vsrc, int buf) {
-    const uint32_t mk = wbase + (uint32_t)buf * (kChunks * 16);
-    const uint32_t mv = wbase + (uint32_t)(kLdsTiles + buf) * (kChunks * 16);
-    dma16(ksrc, voff0, mk);
-    if (kAttnThreads < kChunks) dma16(ksrc, voff1, mk + kAttnThreads * 16);
-    dma16(vsrc, voff0, mv);
-    if (kAttnThreads < kChunks) dma16(vsrc, voff1, mv + kAttnThreads * 16);
-  };
-
-  copy_tile(kc, vc, 0);
-  if (ntiles > 1) copy_tile(kc + kTileElems, vc + kTileElems, 1);
+// The key loop of one path.  `first_tile` runs once tile 0 is resident and its first K fragments
+// are loaded (the general path takes its reference there).  Returns false when the fast path
+// found a row sum it cannot trust.
+template <int kSrc, bool kGen, class FirstTile>
+__device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const KvSource& src,
+                                         int ntiles, int last_valid, int tid, int wave,
+                                         const FragAddr& fa, int g2, FirstTile&& first_tile) {
+  TileCopier<kSrc> copy;
+  copy.init(src, lds, tid, wave);
+  copy.issue(0);
+  if (ntiles > 1) copy.issue(1);
   wait_vm0();
   lds_barrier();
 
   // fill: scores of units 0 .. kQB-2; nothing to multiply by V yet
-  load_k_frags(lds, 0, 0, lane, w.a);
+  load_k_frags<kSrc>(lds, 0, 0, fa, w.a);
+  first_tile();
 #pragma unroll
   for (int i = 0; i < 4; ++i) w.v[i].u = u32x4{0u, 0u, 0u, 0u};
   w.P[0].u = u32x4{0u, 0u, 0u, 0u};
@@ -335,23 +503,19 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
     w.S[qb] = s;
   }
 
-  const uint16_t* ksrc = kc + 2 * (int64_t)kTileElems;  // tile t + 2
-  const uint16_t* vsrc = vc + 2 * (int64_t)kTileElems;
   int t = 0, cur = 0;
   bool ok = true;
   // one iteration = three tiles, so that the LDS buffer of every access is a constant
   for (int round = 0;; ++round) {
-#define AGG_TILE(CUR)                                                                    \
-  if (t + 1 >= ntiles) {                                                                 \
-    cur = CUR;                                                                           \
-    break;                                                                               \
-  }                                                                                      \
-  if (t + 2 < ntiles) copy_tile(ksrc, vsrc, (CUR + 2) % kLdsTiles);                      \
-  ksrc += kTileElems;                                                                    \
-  vsrc += kTileElems;                                                                    \
-  tile_steps<false, kGen>(w, lds, CUR, (CUR + 1) % kLdsTiles, kTileRows, lane, vlane, g2); \
-  wait_vm0();                                                                            \
-  lds_barrier();                                                                         \
+#define AGG_TILE(CUR)                                                                       \
+  if (t + 1 >= ntiles) {                                                                    \
+    cur = CUR;                                                                              \
+    break;                                                                                  \
+  }                                                                                         \
+  if (t + 2 < ntiles) copy.issue((CUR + 2) % kLdsTiles);                                    \
+  tile_steps<kSrc, false, kGen>(w, lds, CUR, (CUR + 1) % kLdsTiles, kTileRows, fa, g2);     \
+  wait_vm0();                                                                               \
+  lds_barrier();                                                                            \
   ++t;
     AGG_TILE(0)
     AGG_TILE(1)
@@ -370,7 +534,7 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
   }
   if (!ok) return false;
   // last tile (runtime buffer number), then the P V of its last unit
-  tile_steps<true, kGen>(w, lds, cur, 0, last_valid, lane, vlane, g2);
+  tile_steps<kSrc, true, kGen>(w, lds, cur, 0, last_valid, fa, g2);
   w.O[kQB - 1][0] = AGG_MFMA(w.v[0], w.P[0], w.O[kQB - 1][0]);
   w.O[kQB - 1][1] = AGG_MFMA(w.v[1], w.P[0], w.O[kQB - 1][1]);
   w.O[kQB - 1][0] = AGG_MFMA(w.v[2], w.P[1], w.O[kQB - 1][0]);
@@ -390,13 +554,15 @@ struct AttnArgs {
   int nqt, npairs;
   const uint32_t* kept_bits;
   const int32_t* nd_dev;
+  const int32_t* list;   // kSrcIndexed: token ids of the keys, [list_stride] per batch element
+  int64_t list_stride;   // 0 when every batch element uses the same list
 };
 
 __shared__ __align__(16) uint16_t smem[2 * kLdsTiles * kTileElems];  // K tiles, then V tiles
 
 // One workgroup's rows by one of the two paths.  Returns false, without storing anything, when
 // the fast path met a row it cannot handle.
-template <bool kGen>
+template <int kSrc, bool kGen>
 __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) {
   const Geom& g = p.g;
   u32x4* lds = reinterpret_cast<u32x4*>(smem);
@@ -405,13 +571,25 @@ __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) 
   const int wave = tid >> 6;
   const int l32 = lane & 31;
   const int g2 = lane >> 5;
-  const int vlane = g2 * 64 + l32;
+  const FragAddr fa = frag_addr(lane);
 
   const int ntiles = (int)(g.M_pad / kTileRows);
   const int last_valid = (int)(g.M - (int64_t)(ntiles - 1) * kTileRows);  // 1..64
-  const int64_t bh_off = ((int64_t)b * g.H + h) * g.M_pad * kHeadDim;
-  const uint16_t* kc = uniform_ptr(p.Kc + bh_off);
-  const uint16_t* vc = uniform_ptr(p.Vc + bh_off);
+  KvSource src;
+  src.rows = g.M;
+  src.row_bytes = (uint32_t)g.H * (kHeadDim * 2);
+  src.max_token = (uint32_t)(g.NQ - 1);
+  if (kSrc == kSrcCompact) {
+    const int64_t bh_off = ((int64_t)b * g.H + h) * g.M_pad * kHeadDim;
+    src.k = uniform_ptr(p.Kc + bh_off);
+    src.v = uniform_ptr(p.Vc + bh_off);
+    src.list = nullptr;
+  } else {
+    const int64_t bh_off = ((int64_t)b * g.NQ * g.H + h) * kHeadDim;
+    src.k = uniform_ptr(p.K + bh_off);
+    src.v = uniform_ptr(p.V + bh_off);
+    src.list = kSrc == kSrcIndexed ? p.list + (int64_t)b * p.list_stride : nullptr;
+  }
 
   Wave w;
   bool dropped[kQB];
@@ -506,12 +684,11 @@ __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) 
   if (!kGen) {
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb) init_extras(qb, 0.f);
-  } else {
-    // reference: the largest of the extras and of the first 32 keys (row 0 always exists),
-    // whose fragments come straight from global memory here
-    const u32x4* k4 = reinterpret_cast<const u32x4*>(kc);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) w.a[ks].u = k4[ks * 64 + lane];
+  }
+  // general path: the reference is the largest of the extras and of the first 32 keys (row 0
+  // always exists); taken when the first tile's K fragments are in registers
+  auto first_tile = [&]() {
+    if (!kGen) return;
     const int valid0 = ntiles == 1 ? last_valid : kTileRows;
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb) {
@@ -531,10 +708,10 @@ __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) 
       w.mref[qb] = mx;
       init_extras(qb, mx);
     }
-  }
+  };
 
-  const bool done =
-      key_loop<kGen>(w, lds, kc, vc, ntiles, last_valid, tid, wave, lane, vlane, g2);
+  const bool done = key_loop<kSrc, kGen>(w, lds, src, ntiles, last_valid, tid, wave, fa, g2,
+                                         first_tile);
   float l_fin[kQB];
   bool unsafe = false;
 #pragma unroll
@@ -617,31 +794,39 @@ __device__ __forceinline__ bool workgroup_tile(const AttnArgs& p, int& b, int& h
   return true;
 }
 
+template <int kSrc>
 __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_kernel(AttnArgs p) {
   int b, h, qt;
   if (!workgroup_tile(p, b, h, qt)) return;
-  if (!attend<false>(p, b, h, qt) && threadIdx.x == 0) *redo_slot(p, b, h, qt) = kRedoMark;
+  if (!attend<kSrc, false>(p, b, h, qt) && threadIdx.x == 0) *redo_slot(p, b, h, qt) = kRedoMark;
 }
 
 // The general path is a kernel of its own, launched behind the first on the same stream: it is
 // rarely needed, starts over from the workgroup's inputs, and this way does not weigh on the
 // register allocation of the fast path.  Workgroups without the mark leave at once.
+template <int kSrc>
 __global__ __launch_bounds__(kAttnThreads, kBlocksPerCu) void sga_attn_general_kernel(AttnArgs p) {
   int b, h, qt;
   if (!workgroup_tile(p, b, h, qt)) return;
   if (*redo_slot(p, b, h, qt) != kRedoMark) return;  // same value in every lane
   __syncthreads();  // every wavefront has read the mark before any of them overwrites it
-  attend<true>(p, b, h, qt);
+  attend<kSrc, true>(p, b, h, qt);
 }
 
 hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bias, const void* Q,
                        const void* K, const void* V, const void* Kc, const void* Vc,
                        const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st,
-                       const uint32_t* kept_bits, const int32_t* nd_dev) {
+                       const uint32_t* kept_bits, const int32_t* nd_dev, int src_mode,
+                       const int32_t* list, int64_t list_stride) {
   const int nqt = (int)((g.NQ + kQTile - 1) / kQTile);
   const int npairs = g.B * g.H;
   const int64_t groups = (int64_t)((npairs + kXcds - 1) / kXcds) * kXcds * nqt;
   if (groups > 0x7FFFFFFF) return hipErrorInvalidConfiguration;
+  // indexed rows are addressed with 32-bit byte offsets from the (batch, head) base, formed by
+  // a 24-bit multiplication of token id and row length
+  if (src_mode == kSrcIndexed && ((uint64_t)g.NQ * g.H * (kHeadDim * 2) > 0xFFFFFFFFull ||
+                                  g.NQ > 0xFFFFFF || (uint64_t)g.H * (kHeadDim * 2) > 0xFFFFFF))
+    return hipErrorInvalidValue;
   (void)hipGetLastError();  // drop any stale error so the check below is this launch's
   AttnArgs p;
   p.g = g;
@@ -661,8 +846,19 @@ hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bi
   p.npairs = npairs;
   p.kept_bits = kept_bits;
   p.nd_dev = nd_dev;
-  hipLaunchKernelGGL(sga_attn_kernel, dim3((unsigned)groups), dim3(kAttnThreads), 0, st, p);
-  hipLaunchKernelGGL(sga_attn_general_kernel, dim3((unsigned)groups), dim3(kAttnThreads), 0, st, p);
+  p.list = list;
+  p.list_stride = list_stride;
+  const dim3 grid((unsigned)groups), block(kAttnThreads);
+  if (src_mode == kSrcCompact) {
+    hipLaunchKernelGGL(sga_attn_kernel<kSrcCompact>, grid, block, 0, st, p);
+    hipLaunchKernelGGL(sga_attn_general_kernel<kSrcCompact>, grid, block, 0, st, p);
+  } else if (src_mode == kSrcRows) {
+    hipLaunchKernelGGL(sga_attn_kernel<kSrcRows>, grid, block, 0, st, p);
+    hipLaunchKernelGGL(sga_attn_general_kernel<kSrcRows>, grid, block, 0, st, p);
+  } else {
+    hipLaunchKernelGGL(sga_attn_kernel<kSrcIndexed>, grid, block, 0, st, p);
+    hipLaunchKernelGGL(sga_attn_general_kernel<kSrcIndexed>, grid, block, 0, st, p);
+  }
   return hipGetLastError();
 }
 

@@ -428,21 +428,36 @@ __global__ __launch_bounds__(kFinalCols * kFinalGroups) void mean_final_kernel(
   }
 }
 
-// Enqueues the gather (+ index list) and, when kmean/vmean are given, the mean terms.
+// The index list alone (when no compacted copy is wanted): one thread per kept row.
+__global__ __launch_bounds__(kSubThreads) void index_kernel(Geom g, int32_t* __restrict__ idx) {
+  const int64_t m = (int64_t)blockIdx.x * kSubThreads + threadIdx.x;
+  if (m < g.M) idx[m] = (int32_t)kept_row_to_token(g, m);
+}
+
+// Enqueues the gather (+ index list) and, when kmean/vmean are given, the mean terms.  Without
+// Kc/Vc only the index list and the mean terms are produced.
 hipError_t launch_subsample(const Geom& g, const void* K, const void* V, void* Kc, void* Vc,
                             int32_t* idx, float* kmean, float* vmean, void* workspace,
                             hipStream_t st) {
   const bool want_mean = (kmean != nullptr);
+  const bool want_copy = (Kc != nullptr);
   const MeanPlan plan = mean_plan(g);
   const int nhg = (g.H + kHeadGroup - 1) / kHeadGroup;
-  const int64_t n_gather = (g.M_pad / kTileRows) * nhg;
+  const int64_t n_gather = want_copy ? (g.M_pad / kTileRows) * nhg : 0;
   const int64_t n_mean = want_mean ? (int64_t)plan.nchunks * plan.ncolblk : 0;
   const int64_t groups = (n_gather + n_mean) * g.B;
   if (groups > 0x7FFFFFFF || n_gather > 0x3FFFFFFF) return hipErrorInvalidConfiguration;
   (void)hipGetLastError();  // drop any stale error so the check below is this launch's
-  hipLaunchKernelGGL(subsample_kernel, dim3((unsigned)groups), dim3(kSubThreads), 0, st, g,
-                     (const uint16_t*)K, (const uint16_t*)V, (uint16_t*)Kc, (uint16_t*)Vc, idx,
-                     (float*)workspace, plan, (int)n_mean, (int)n_gather, nhg);
+  if (!want_copy && idx) {
+    hipLaunchKernelGGL(index_kernel, dim3((unsigned)((g.M + kSubThreads - 1) / kSubThreads)),
+                       dim3(kSubThreads), 0, st, g, idx);
+    hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return e0;
+  }
+  if (groups > 0)
+    hipLaunchKernelGGL(subsample_kernel, dim3((unsigned)groups), dim3(kSubThreads), 0, st, g,
+                       (const uint16_t*)K, (const uint16_t*)V, (uint16_t*)Kc, (uint16_t*)Vc, idx,
+                       (float*)workspace, plan, (int)n_mean, (int)n_gather, nhg);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !want_mean) return e;
   const int C = g.H * kHeadDim;

@@ -121,7 +121,12 @@ hipError_t launch_subsample(const Geom& g, const void* K, const void* V, void* K
 hipError_t launch_attn(const Geom& g, uint32_t flags, float scale, float mean_bias, const void* Q,
                        const void* K, const void* V, const void* Kc, const void* Vc,
                        const float* kmean, const float* vmean, void* O, float* lse, hipStream_t st,
-                       const uint32_t* kept_bits = nullptr, const int32_t* nd_dev = nullptr);
+                       const uint32_t* kept_bits = nullptr, const int32_t* nd_dev = nullptr,
+                       int src_mode = 0, const int32_t* list = nullptr, int64_t list_stride = 0);
+// src_mode of launch_attn: where the key/value tiles come from
+enum { kAttnSrcCompact = 0,   // Kc/Vc in fragment order
+       kAttnSrcRows = 1,      // every token of K/V, in place (ordinary and per-frame attention)
+       kAttnSrcIndexed = 2 }; // the rows of K/V that `list` names, in place
 
 // Caller-supplied kept lists: g.M / g.M_pad hold the list length.
 int64_t list_words(const Geom& g);               // uint32 words of one batch element's bitmap

@@ -107,6 +107,12 @@ def attend(buf: SgaBuffers, Q, K, V, stream=None):
                             buf.lse, stream)
 
 
+def attend_idx(buf: SgaBuffers, Q, K, V, stream=None):
+    """The same attention reading the kept rows of K/V in place through buf.idx."""
+    agg.agg_global_attn_fwd_idx(buf.shape, Q, K, V, buf.idx, buf.kmean, buf.vmean, buf.O, buf.lse,
+                                stream)
+
+
 def sga_forward(shape, Q, K, V, poison=False) -> SgaBuffers:
     """One pass of the whole path: gather + mean terms, then attention."""
     buf = alloc(shape, Q.device, poison=poison)
@@ -119,9 +125,7 @@ def dense_forward(shape, Q, K, V, with_lse=True):
     B, H, D, NQ = shape.B, shape.H, shape.D, shape.NQ
     O = _buf((B, NQ, H, D), torch.bfloat16, Q.device, "dense O")
     lse = _buf((B, H, NQ), torch.float32, Q.device, "dense lse") if with_lse else None
-    nws = agg.agg_dense_workspace_bytes(shape)
-    ws = _buf(nws, torch.uint8, Q.device, "dense workspace")
-    agg.agg_dense_global_attn_fwd(shape, Q, K, V, O, lse, ws, nws)
+    agg.agg_dense_global_attn_fwd(shape, Q, K, V, O, lse)
     return O, lse
 
 
@@ -130,9 +134,7 @@ def frame_forward(shape, Q, K, V, with_lse=True):
     B, N, H, D, NQ = shape.B, shape.N, shape.H, shape.D, shape.NQ
     O = _buf((B, NQ, H, D), torch.bfloat16, Q.device, "frame O")
     lse = _buf((B * N, H, shape.L), torch.float32, Q.device, "frame lse") if with_lse else None
-    nws = agg.agg_frame_workspace_bytes(shape)
-    ws = _buf(nws, torch.uint8, Q.device, "frame workspace")
-    agg.agg_frame_attn_fwd(shape, Q, K, V, O, lse, ws, nws)
+    agg.agg_frame_attn_fwd(shape, Q, K, V, O, lse)
     return O, lse
 
 

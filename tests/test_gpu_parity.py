@@ -304,6 +304,61 @@ def test_full_size_dense_baseline():
 
 
 # ----------------------------------------------------------------------------
+# The same attention with the kernel fetching the kept rows of K/V in place through the index
+# list (no compacted copy): identical arithmetic on identical operands, so bit-identical results.
+# ----------------------------------------------------------------------------
+def _idx_case(shape, q, k, v, what):
+    say("idx case %s: N=%d grid=%dx%d H=%d strides=(%d,%d) keep_first=%d flags=%d" % (
+        what, shape.N, shape.n_h, shape.n_w, shape.H, shape.s_h, shape.s_w, shape.keep_first_frame,
+        shape.flags))
+    ref = harness.sga_forward(shape, q, k, v, poison=True)
+    got = harness.alloc(shape, "cuda", poison=True)
+    # index list and mean terms only: no compacted tensors are written or read
+    agg.agg_kv_subsample(shape, k, v, None, None, got.idx, got.kmean, got.vmean, got.workspace,
+                         got.workspace.numel())
+    harness.attend_idx(got, q, k, v)
+    torch.cuda.synchronize()
+    assert torch.equal(ref.idx, got.idx)
+    assert torch.equal(ref.kmean, got.kmean) and torch.equal(ref.vmean, got.vmean)
+    assert torch.isnan(got.Kc.float()).all() and torch.isnan(got.Vc.float()).all()  # untouched
+    assert torch.equal(ref.O.view(torch.int16), got.O.view(torch.int16)), what
+    assert torch.equal(ref.lse, got.lse), what
+
+
+@pytest.mark.parametrize("sigma,keep_first,flags", [(2, 1, 3), (4, 0, 3), (9, 1, 1), (6, 0, 2),
+                                                    (4, 1, 0), (1, 1, 3)])
+def test_idx_path_matches_compacted_path_tiny(tiny_qkv, sigma, keep_first, flags):
+    w, (q, k, v) = tiny_qkv
+    s_h, s_w = agg.agg_sigma_to_strides(sigma)
+    _idx_case(harness.shape_of(w, flags=flags, s_h=s_h, s_w=s_w, keep_first_frame=keep_first),
+              q, k, v, "tiny")
+
+
+@pytest.mark.parametrize("case", RAGGED)
+def test_idx_path_matches_compacted_path_ragged(case):
+    B, N, n_h, n_w, P, H, s_h, s_w, kf = case
+    shape = agg.make_shape(B, N, n_h, n_w, P, H, 64, s_h, s_w, kf)
+    q, k, v = inputs.iid_qkv(B, shape.NQ, H, 64, seed=500 + N * 7 + H, device="cuda")
+    _idx_case(shape, q, k, v, "ragged")
+
+
+def test_idx_path_extreme_logits():
+    """The general path of the index-driven kernel (own key at several hundred nats)."""
+    shape = agg.make_shape(1, 3, 9, 7, 5, 3, 64, 2, 2, 1)
+    q, k, v = inputs.iid_qkv(1, shape.NQ, 3, 64, seed=4242, device="cuda")
+    qf = q.float()
+    qf[:, ::5] = 40.0 * k.float()[:, ::5]
+    _idx_case(shape, qf.to(torch.bfloat16), k, v, "extreme")
+
+
+def test_idx_path_full_size():
+    """100 frames, every output row: bit-identical to the compacted path."""
+    w = inputs.WORKLOADS["f100"]
+    q, k, v = inputs.make_qkv(w, "cuda")
+    _idx_case(harness.shape_of(w), q, k, v, "f100")
+
+
+# ----------------------------------------------------------------------------
 # Frame attention (Global-to-Frame conversion of early global blocks)
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("case", [(2, 3, 5, 7, 2, 3), (1, 4, 16, 16, 5, 16), (1, 2, 37, 37, 5, 2)])

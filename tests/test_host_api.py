@@ -141,24 +141,27 @@ def test_error_paths_before_any_launch():
     bad = agg.make_shape(1, 2, 16, 16, 5, 16, 32, 2, 2)
     assert att(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, fake, fake, None, None) == -3
     den = lib.agg_dense_global_attn_fwd
-    dws = agg.agg_dense_workspace_bytes(good)
-    assert dws == 2 * 1 * 16 * 576 * 64 * 2  # 522 rows padded to 576
-    assert den(ctypes.byref(good), fake, fake, fake, fake, None, None, dws, None) == -1
-    assert den(ctypes.byref(good), fake, fake, fake, fake, None, fake, dws - 1, None) == -5
-    assert den(ctypes.byref(good), fake, fake, fake, odd, None, fake, dws, None) == -4
+    assert den(ctypes.byref(good), fake, fake, fake, None, None, None) == -1
+    assert den(ctypes.byref(good), fake, fake, fake, odd, None, None) == -4
+    assert den(ctypes.byref(bad), fake, fake, fake, fake, None, None) == -3
 
-    # frame attention and the block: same validation before any launch
-    fws = agg.agg_frame_workspace_bytes(good)
-    assert fws == 2 * 2 * 16 * 320 * 64 * 2  # 2 frames of 261 tokens, each padded to 320 rows
+    # frame attention, the index-driven call and the block: same validation before any launch
     fr = lib.agg_frame_attn_fwd
-    assert fr(ctypes.byref(good), fake, fake, fake, fake, None, None, fws, None) == -1
-    assert fr(ctypes.byref(good), fake, fake, fake, fake, None, fake, fws - 1, None) == -5
+    assert fr(ctypes.byref(good), fake, fake, None, fake, None, None) == -1
+    assert fr(ctypes.byref(good), fake, odd, fake, fake, None, None) == -4
+    ix = lib.agg_global_attn_fwd_idx
+    assert ix(ctypes.byref(good), fake, fake, fake, None, fake, fake, fake, None, None) == -1
+    assert ix(ctypes.byref(good), fake, fake, fake, fake, fake, odd, fake, None, None) == -4
+    far = agg.make_shape(1, 13000, 37, 37, 5, 16, 64, 2, 2)   # 17.9 M tokens: beyond 24-bit ids
+    assert ix(ctypes.byref(far), fake, fake, fake, fake, fake, fake, fake, None, None) == -6
+    # the subsample call takes both compacted tensors or neither
+    assert sub(ctypes.byref(good), fake, fake, None, fake, None, fake, fake, fake, ws, None) == -1
     w = agg.agg_block_weights(0x1000, 0x1000, 1e-6, 0x1000, 0x1000, 0x1000, 0x1000, None, None,
                               None, None)
     blk = lib.agg_global_block_fwd
     for mode in (agg.AGG_BLOCK_SGA, agg.AGG_BLOCK_FRAME, agg.AGG_BLOCK_DENSE):
         bws = agg.agg_block_workspace_bytes(good, mode)
-        assert bws > 5 * 522 * 1024 * 2
+        assert bws >= 5 * 522 * 1024 * 2   # five activations; SGA adds its compacted set
         other = ctypes.c_void_p(0x2000)
         assert blk(ctypes.byref(good), mode, ctypes.byref(w), fake, other, fake, bws - 1, None) == -5
         assert blk(ctypes.byref(good), mode, ctypes.byref(w), None, other, fake, bws, None) == -1
