@@ -101,6 +101,26 @@ def run_workload(name, steps, warmup, dense, log):
     res.update({"ms_attn_idx": ms_idx, "tflops_attn_idx": flops / (ms_idx * 1e-3) / 1e12})
     del Oi
     if dense:
+        # what a fallback costs: one query in 256 gets logits far outside the fast path's window,
+        # so EVERY workgroup redoes its rows in the general path (second kernel of the call)
+        qx = q.clone()
+        qx[:, ::256] *= 64.0
+        Ox = buf.O
+        buf.O = torch.empty_like(Ox)
+        ms_fb, _ = time_events(lambda: harness.attend(buf, qx, k, v), max(2, min(steps, 3)), 1)
+        buf.O = Ox
+        del qx
+        res["general_path"] = {
+            "what": "attention launch with every workgroup falling back to the general path "
+                    "(one query in 256 scaled by 64)",
+            "ms_attn_all_fallback": ms_fb, "ms_attn_fast": ms_attn,
+            "ratio": ms_fb / ms_attn, "tflops_all_fallback": flops / (ms_fb * 1e-3) / 1e12}
+        # a plain device copy of 1 GiB: the HBM rate this part reaches (read + write bytes)
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        ms_copy, _ = time_events(lambda: dst.copy_(src), 5, 2)
+        res["copy_gbs"] = 2.0 * src.numel() * 4 / (ms_copy * 1e-3) / 1e9
+        del src, dst
         Od = torch.empty_like(buf.O)
 
         def dense_step():
@@ -285,30 +305,28 @@ def run_sweep(args, log):
     return 0
 
 
-def run_block(args, log):
-    """The global-attention blocks of one aggregator pass at full width (dim 1024 = 16 x 64):
-    LayerNorm, Q/K/V projections, attention, output projection and residual per block;
-    `--layers` blocks chained, the first `--t-early` of them as per-frame attention
-    (Global-to-Frame conversion, Sec. 4.2), the rest subsampled (Sec. 4.3).  One dense
-    block is timed beside them for the ratio.  Random-init weights, one set per layer."""
+def time_block_stack(workload, layers_n, t_early, t_end, steps, warmup, with_dense, log):
+    """Times the chained global-attention blocks on `workload` (see run_block) and returns a
+    dict: ms per pass over the stack, one block of each kind alone, and the attention and gather
+    launches of a subsampled block alone (what remains is LayerNorm + projections)."""
     import torch
 
     from paper_2512_02541_amd import binding as agg
     from paper_2512_02541_amd import harness, inputs
 
-    w = inputs.WORKLOADS[args.workload]
+    w = inputs.WORKLOADS[workload]
     shape = harness.shape_of(w)
     C = w.H * w.D
     log("block stack on %s: %d tokens x %d channels, %d layers (%d as frame attention)" % (
-        args.workload, w.NQ, C, args.layers, args.t_early))
+        workload, w.NQ, C, layers_n, t_early))
     x0 = inputs.block_input(w.B, w.NQ, C, w.seed, "cuda")
-    layers = [inputs.block_weights(C, w.seed + 1 + i, "cuda") for i in range(args.layers)]
+    layers = [inputs.block_weights(C, w.seed + 1 + i, "cuda") for i in range(layers_n)]
     cws = [agg.make_block_weights(l["ln_gamma"], l["ln_beta"], l["ln_eps"], l["w_q"], l["w_k"],
                                   l["w_v"], l["w_o"], l["b_q"], l["b_k"], l["b_v"], l["b_o"])
            for l in layers]
-    t_end = args.layers - 1 if args.t_end is None else args.t_end
-    modes = [agg.AGG_BLOCK_FRAME if (i < args.t_early or i > t_end) else agg.AGG_BLOCK_SGA
-             for i in range(args.layers)]
+    t_end = layers_n - 1 if t_end is None else t_end
+    modes = [agg.AGG_BLOCK_FRAME if (i < t_early or i > t_end) else agg.AGG_BLOCK_SGA
+             for i in range(layers_n)]
     n_frame = sum(m == agg.AGG_BLOCK_FRAME for m in modes)
     nws = max(agg.agg_block_workspace_bytes(shape, m) for m in
               (agg.AGG_BLOCK_FRAME, agg.AGG_BLOCK_SGA, agg.AGG_BLOCK_DENSE))
@@ -317,56 +335,80 @@ def run_block(args, log):
 
     def stack():
         src = x0
-        for i in range(args.layers):
+        for i in range(layers_n):
             dst = xa if (i % 2 == 0) else xb
             agg.agg_global_block_fwd(shape, modes[i], cws[i], src, dst, ws, nws)
             src = dst
         return src
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         stack()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         out = stack()
     torch.cuda.synchronize()
-    ms_stack = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_stack = (time.perf_counter() - t0) * 1e3 / steps
     finite = bool(torch.isfinite(out[:, ::997].float()).all().item())
 
     def one(mode, n):
         return time_events(lambda: agg.agg_global_block_fwd(shape, mode, cws[-1], x0, xa, ws, nws),
                            n, 1)[0]
 
-    ms_sga = one(agg.AGG_BLOCK_SGA, args.steps)
-    ms_frame = one(agg.AGG_BLOCK_FRAME, args.steps)
-    ms_dense = one(agg.AGG_BLOCK_DENSE, 1) if not args.no_dense else None
+    ms_sga = one(agg.AGG_BLOCK_SGA, steps)
+    ms_frame = one(agg.AGG_BLOCK_FRAME, steps)
+    ms_dense = one(agg.AGG_BLOCK_DENSE, 1) if with_dense else None
+    # the attention-side launches of one block alone, on the block's own Q/K/V (left in the
+    # workspace by the last call: five [B, NQ, C] activations, then the attention scratch)
+    act = (w.B * w.NQ * C * 2 + 255) // 256 * 256
+    qv, kv, vv = (ws[i * act:i * act + w.B * w.NQ * C * 2].view(torch.bfloat16).view(
+        w.B, w.NQ, w.H, w.D) for i in (1, 2, 3))
+    buf = harness.alloc(shape, "cuda", with_lse=False)
+    ms_gather = time_events(lambda: harness.subsample(buf, kv, vv), steps, 1)[0]
+    ms_attn = time_events(lambda: harness.attend(buf, qv, kv, vv), steps, 1)[0]
+    ms_fattn = time_events(lambda: agg.agg_frame_attn_fwd(shape, qv, kv, vv, buf.O, None), steps, 1)[0]
     M, _ = agg.agg_kv_count(shape)
     proj_flops = 4 * 2.0 * w.NQ * C * C
-    fl_sga = sga_flops(w.NQ, M, w.H, w.D) + proj_flops
+    fl_attn = sga_flops(w.NQ, M, w.H, w.D)
+    fl_sga = fl_attn + proj_flops
     fl_frame = 4.0 * w.N * w.L * w.L * w.D * w.H + proj_flops
-    fl_stack = n_frame * fl_frame + (args.layers - n_frame) * fl_sga
+    fl_stack = n_frame * fl_frame + (layers_n - n_frame) * fl_sga
+    return {
+        "workload": "%s block stack: %d frames x (37x37+5) tokens, dim %d, %d global blocks, first "
+                    "%d%s as frame attention, rest subsampled with strides (%d,%d), diag+mean" % (
+                        workload, w.N, C, layers_n, t_early,
+                        "" if t_end == layers_n - 1 else " and those above index %d" % t_end,
+                        w.s_h, w.s_w),
+        "NQ": w.NQ, "M": M, "passes_timed": steps, "ms_stack": ms_stack,
+        "ms_block_sga": ms_sga, "ms_block_frame": ms_frame, "ms_block_dense": ms_dense,
+        "ms_sga_attention_kernel": ms_attn, "ms_sga_gather": ms_gather,
+        "ms_frame_attention_kernel": ms_fattn,
+        "ms_layernorm_and_projections": ms_sga - ms_attn - ms_gather,
+        "frac_peak_sga_attention": fl_attn / (ms_attn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "tflops_block_sga": fl_sga / (ms_sga * 1e-3) / 1e12,
+        "tflops_block_frame": fl_frame / (ms_frame * 1e-3) / 1e12,
+        "tflops_stack": fl_stack / (ms_stack * 1e-3) / 1e12,
+        "projection_flops_per_block": proj_flops,
+        "ms_stack_if_all_dense": (ms_dense * layers_n) if ms_dense else None,
+        "speedup_vs_all_dense": (ms_dense * layers_n / ms_stack) if ms_dense else None,
+        "output_finite": finite,
+    }
+
+
+def run_block(args, log):
+    """The global-attention blocks of one aggregator pass at full width (dim 1024 = 16 x 64):
+    LayerNorm, Q/K/V projections, attention, output projection and residual per block;
+    `--layers` blocks chained, the first `--t-early` of them as per-frame attention
+    (Global-to-Frame conversion, Sec. 4.2), the rest subsampled (Sec. 4.3).  One dense
+    block is timed beside them for the ratio.  Random-init weights, one set per layer."""
+    r = time_block_stack(args.workload, args.layers, args.t_early, args.t_end, args.steps,
+                         args.warmup, not args.no_dense, log)
     res = {
         "metric": "ms per aggregator pass over the global-attention blocks (LayerNorm + QKV "
                   "projection + attention + output projection + residual)",
-        "value": ms_stack, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_stack, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s block stack: %d frames x (37x37+5) tokens, dim %d, %d global "
-                               "blocks, first %d%s as frame attention, rest subsampled with strides "
-                               "(%d,%d), diag+mean" % (args.workload, w.N, C, args.layers,
-                                                       args.t_early,
-                                                       "" if args.t_end is None else
-                                                       " and those above index %d" % args.t_end,
-                                                       w.s_h, w.s_w),
-                   "NQ": w.NQ, "M": M, "ms_block_sga": ms_sga, "ms_block_frame": ms_frame,
-                   "ms_block_dense": ms_dense,
-                   "tflops_block_sga": fl_sga / (ms_sga * 1e-3) / 1e12,
-                   "tflops_block_frame": fl_frame / (ms_frame * 1e-3) / 1e12,
-                   "tflops_stack": fl_stack / (ms_stack * 1e-3) / 1e12,
-                   "projection_flops_per_block": proj_flops,
-                   "ms_stack_if_all_dense": (ms_dense * args.layers) if ms_dense else None,
-                   "speedup_vs_all_dense": (ms_dense * args.layers / ms_stack) if ms_dense else None,
-                   "output_finite": finite},
+        "value": r["ms_stack"], "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": r["ms_stack"], "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "config": r,
     }
     print(json.dumps(res), flush=True)
     return 0
@@ -382,6 +424,8 @@ def main():
                     help="comma list of further workloads timed (SGA only) into config.also")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-block", action="store_true",
+                    help="skip the 12-block stack at 333 frames (config.block_f333)")
     ap.add_argument("--cpu-rows", type=int, default=1024)
     ap.add_argument("--sweep", action="store_true",
                     help="time the method's variants on --workload (sigma 2/4/6/9, both first-frame "
@@ -441,6 +485,12 @@ def main():
                                        "ms_gather", "ms_attn", "tflops_attn", "frac_peak_attn",
                                        "gather_gbs", "ms_attn_idx")})
 
+    block = None
+    if not args.no_block:
+        # BASELINE config 5: 12 global blocks at 333 frames, the first 4 as frame attention
+        block = time_block_stack("f333", 12, 4, None, 2, 1, False, log)
+        torch.cuda.empty_cache()
+
     out = {
         "metric": METRIC,
         "value": res["tflops_layer"], "unit": "TFLOP/s",
@@ -454,6 +504,7 @@ def main():
                    "NQ": res["NQ"], "M": res["M"], "n_dropped": res["n_dropped"],
                    "ms_gather": res["ms_gather"], "ms_attn": res["ms_attn"],
                    "gather_gbs": res["gather_gbs"], "gather_frac_hbm": res["gather_frac_hbm"],
+                   "copy_gbs": res.get("copy_gbs"), "general_path": res.get("general_path"),
                    "frac_bf16_peak_layer": res["tflops_layer"] / PEAK_BF16_TFLOPS,
                    "ms_dense": res.get("ms_dense"), "tflops_dense": res.get("tflops_dense"),
                    "ms_frame_attn": res.get("ms_frame_attn"),
@@ -464,7 +515,7 @@ def main():
                    "ideal_speedup": res.get("ideal_speedup"),
                    "paper_context": "end-to-end speedups ~2x/4-5x/8-10x at 100/300/800 frames on "
                                     "A100-80GB with FlashAttention-2 (whole model, not this layer)",
-                   "also": also, "parity_vs_oracle": parity},
+                   "also": also, "block_f333": block, "parity_vs_oracle": parity},
         "roofline": {"bound": "mfma", "achieved": res["tflops_attn"], "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": res["frac_peak_attn"],
                      "traffic": read_traffic(res["workload"]),
