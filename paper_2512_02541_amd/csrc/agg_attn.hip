@@ -35,12 +35,14 @@
 //     redo its rows in the general path (a second kernel behind this one, see
 //     the end of the file); ordinary attention logits never get there.  The
 //     sums are checked every few tiles, so an overflow ends the fast pass early.
-//   * General path: the same pipeline with a per-row reference that is subtracted
-//     before the exponential.  The reference starts at the largest of the extras
-//     and the first 32 keys and is raised lazily: a unit's row sums show when a
-//     score exceeds it by more than 2^100; only then (a rare, wavefront-uniform
-//     branch) is the unit's maximum taken, the accumulator rescaled and the
-//     unit redone.  No running maximum is computed otherwise.
+//   * General path: the same pipeline with a per-row reference, subtracted by the
+//     matrix core (a fifth, rank-2 product per unit adds minus the reference to
+//     the scores), so the vector ALU does no more per score than on the fast
+//     path.  The reference starts at the largest of the extras and the first 32
+//     keys and is raised lazily: a unit's row sums show when a score exceeds it
+//     by more than 2^100; only then (a rare, wavefront-uniform branch) is the
+//     unit's maximum taken, the accumulator rescaled and the unit redone.  No
+//     running maximum is computed otherwise.
 //   * The zero-padded rows of the last tile are masked there (the last tile is
 //     peeled), nowhere else.
 //   * The extras enter as the initial state (sum, accumulator) of either path, so
@@ -173,6 +175,7 @@ struct Wave {
   f32x16 S[kQB];       // score tiles in flight
   float la[kQB][2];    // two partial row sums per query block
   float mref[kQB];     // general path: the row's reference (base-2 logit)
+  Frag mneg[kQB];      // general path: minus that reference as a B operand (see set_reference)
   Frag a[4];           // K fragments of the 32-key block whose scores are being computed
   Frag v[4];           // V fragments of the block whose P V is being accumulated; hf*2 + db
   Frag P[2];           // probabilities of the previous unit
@@ -370,6 +373,22 @@ struct TileCopier {
   }
 };
 
+// General path: the row reference is subtracted by the matrix core.  A fifth product per unit
+// adds  ones(32 keys x 16) * R(16 x 32 queries)  to the scores, where column q of R holds
+// -(m_hi, m_lo, 0, ...) and m_hi + m_lo -- two bf16 values -- IS the reference: the reference is
+// whatever that sum comes to (exactly representable in float), so nothing is lost by the split.
+__device__ __forceinline__ void set_reference(Wave& w, int qb, float m, int g2) {
+  const float hi = bf16_lo(pack_bf16(m, 0.f));
+  const float lo = bf16_lo(pack_bf16(m - hi, 0.f));
+  w.mref[qb] = hi + lo;
+  w.mneg[qb].u = u32x4{g2 == 0 ? pack_bf16(-hi, -lo) : 0u, 0u, 0u, 0u};
+}
+__device__ __forceinline__ Frag ones_frag(int g2) {
+  Frag f;
+  f.u = u32x4{g2 == 0 ? 0x3F803F80u : 0u, 0u, 0u, 0u};  // bf16 (1, 1) in contraction slots 0, 1
+  return f;
+}
+
 // One step of the pipeline inside tile `cur` (see the file header).  kLast: the tile is the
 // last one (`valid` of its 64 rows exist, nothing follows).  kGen: general path.
 template <int kSrc, bool kLast, bool kGen>
@@ -391,6 +410,10 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
       f32x16 z;
 #pragma unroll
       for (int r = 0; r < 16; ++r) z[r] = 0.f;
+      if (kGen) {  // scores relative to the row's reference
+        const Frag one = ones_frag(g2);
+        z = AGG_MFMA(one, w.mneg[tq], z);
+      }
       Sn = AGG_MFMA(w.a[0], w.Qf[tq][0], z);
 #pragma unroll
       for (int ks = 1; ks < 4; ++ks) Sn = AGG_MFMA(w.a[ks], w.Qf[tq][ks], Sn);
@@ -402,51 +425,16 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
 
     // ---- vector ALU: probabilities of unit sg ----
     Frag Pn[2];
+    float u0 = 0.f, u1 = 0.f;  // general path: the unit's own row sums
     {
       f32x16& S = w.S[qb];
       if (kLast && valid < kTileRows) mask16(S, kb, valid, g2);
       if (!kGen) {
         exp16(S, Pn, w.la[qb][0], w.la[qb][1]);
       } else {
-        // probabilities relative to the row's reference; the unit's own sums tell whether the
-        // reference still holds (a score more than 2^100 above it cannot hide in them)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) S[r] -= w.mref[qb];
-        float u0 = 0.f, u1 = 0.f;
+        // the scores are already relative to the row's reference; whether it still holds is
+        // looked at below, behind the step's last MFMA
         exp16(S, Pn, u0, u1);
-        if (__builtin_amdgcn_ballot_w64(!(u0 + u1 < kUnitHi)) != 0) {
-          // rare: recompute the unit's scores from the tile (still resident), raise the reference
-          // of the rows that need it (factor 1 for the others), scale what they have accumulated,
-          // and redo the unit
-          f32x16 R;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) R[r] = 0.f;
-          Frag kf[4];
-          load_k_frags<kSrc>(lds, cur, kb, fa, kf);
-#pragma unroll
-          for (int ks = 0; ks < 4; ++ks) R = AGG_MFMA(kf[ks], w.Qf[qb][ks], R);
-          if (kLast && valid < kTileRows) mask16(R, kb, valid, g2);
-          float mx = R[0];
-#pragma unroll
-          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, R[r]);
-          mx = pair_max(mx) - w.mref[qb];
-          const float d = mx > kLazy ? mx : 0.f;
-          const float f = fast_exp2(-d);
-          w.mref[qb] += d;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            R[r] -= w.mref[qb];
-            w.O[qb][0][r] *= f;
-            w.O[qb][1][r] *= f;
-          }
-          w.la[qb][0] *= f;
-          w.la[qb][1] *= f;
-          u0 = 0.f;
-          u1 = 0.f;
-          exp16(R, Pn, u0, u1);
-        }
-        w.la[qb][0] += u0;
-        w.la[qb][1] += u1;
       }
     }
     if (do_qk) w.S[tq] = Sn;
@@ -462,13 +450,44 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
     // Issue order inside the step: one MFMA, then its share of the vector work (two
     // exponentials, one conversion, two additions).  Left to itself the scheduler bunches the
     // MFMAs, and the wavefront then stalls on the matrix pipe with vector work still to issue.
+    if (kGen) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // the reference product
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
       __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);  // transcendental
-      __builtin_amdgcn_sched_group_barrier(0x002, kGen ? 5 : 3, 0);  // other vector ALU
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // other vector ALU
     }
     __builtin_amdgcn_sched_barrier(0);
+    if (kGen) {
+      // The unit's sums tell whether the reference still holds: a score more than 2^100 above it
+      // cannot hide in them.  Rare, wavefront-uniform: raise the reference of the rows that need
+      // it (the others keep theirs: shift 0, factor 1), scale what they have accumulated, and
+      // redo the unit's probabilities (its scores are untouched until the next step).
+      if (__builtin_amdgcn_ballot_w64(!(u0 + u1 < kUnitHi)) != 0) {
+        f32x16& S = w.S[qb];
+        float mx = S[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[r]);
+        mx = pair_max(mx);  // both lanes of a row agree
+        const float old = w.mref[qb];
+        if (mx > kLazy) set_reference(w, qb, old + mx, g2);
+        const float d = w.mref[qb] - old;
+        const float f = fast_exp2(-d);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          S[r] -= d;
+          w.O[qb][0][r] *= f;
+          w.O[qb][1][r] *= f;
+        }
+        w.la[qb][0] *= f;
+        w.la[qb][1] *= f;
+        u0 = 0.f;
+        u1 = 0.f;
+        exp16(S, w.P, u0, u1);
+      }
+      w.la[qb][0] += u0;
+      w.la[qb][1] += u1;
+    }
   }
 }
 
@@ -498,6 +517,10 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    if (kGen) {
+      const Frag one = ones_frag(g2);
+      s = AGG_MFMA(one, w.mneg[qb], s);
+    }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) s = AGG_MFMA(w.a[ks], w.Qf[qb][ks], s);
     w.S[qb] = s;
@@ -705,8 +728,8 @@ __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) 
       mx = fmaxf(mx, fmaxf(l_self[qb], l_mean[qb]));
       // a NaN or infinite score cannot serve as reference; the row's result is NaN anyway
       if (!(fabsf(mx) < 3.0e38f)) mx = 0.f;
-      w.mref[qb] = mx;
-      init_extras(qb, mx);
+      set_reference(w, qb, mx, g2);
+      init_extras(qb, w.mref[qb]);
     }
   };
 
