@@ -212,6 +212,7 @@ def run_only(args, log):
         return 0
     w = inputs.WORKLOADS[args.workload]
     shape = harness.shape_of(w)
+    log("generating %s (%s)" % (args.workload, args.data))
     if args.data == "zeros":      # same launches on all-zero tensors: isolates the effect of the
         q = k = v = torch.zeros((w.B, w.NQ, w.H, w.D), dtype=torch.bfloat16, device="cuda")  # chip's power management
     elif args.data == "iid":
@@ -223,6 +224,7 @@ def run_only(args, log):
     buf = harness.alloc(shape, "cuda")
     harness.subsample(buf, k, v)
     torch.cuda.synchronize()
+    log("inputs ready; launching %s x %d" % (args.only, args.steps))
     if args.only == "attn" and args.steps >= 5:
         ms, mn = time_events(lambda: harness.attend(buf, q, k, v), args.steps, 2)
         fl = sga_flops(w.NQ, buf.M, w.H, w.D)
@@ -231,14 +233,15 @@ def run_only(args, log):
                           "tflops_attn": fl / (ms * 1e-3) / 1e12,
                           "frac_peak": fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}))
         return 0
-    for _ in range(args.steps):
+    for i in range(args.steps):
         if args.only == "attn":
             harness.attend(buf, q, k, v)
         elif args.only == "gather":
             harness.subsample(buf, k, v)
         else:
             agg.agg_dense_global_attn_fwd(shape, q, k, v, buf.O, None)
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        log("launch %d done" % i)
     print(json.dumps({"only": args.only, "workload": args.workload, "launches": args.steps,
                       "flops_per_launch": sga_flops(w.NQ, buf.M, w.H, w.D),
                       "gather_bytes": 2.0 * w.NQ * w.H * w.D * 2 + 2.0 * buf.M * w.H * w.D * 2}))
