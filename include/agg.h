@@ -82,7 +82,9 @@ int agg_sigma_to_strides(int sigma, int32_t* s_h, int32_t* s_w);
  * n_dropped = number of patch tokens left out (Sec. 4.3).  Either output may be NULL. */
 int agg_kv_count(const agg_shape* shape, int64_t* M, int64_t* n_dropped);
 
-/* Host only.  Writes the ascending token ids of the kept set into idx[M] (host memory). */
+/* Host only.  The index set of Sec. 4.3 (special tokens, the reference frame when kept whole,
+ * the first patch of every s_h x s_w window), as ascending token ids, into idx[M] (host memory):
+ * what agg_kv_subsample writes on the device. */
 int agg_kv_indices_host(const agg_shape* shape, int32_t* idx);
 
 /* Host only.  Writes the ascending token ids of the dropped patches (the set the mean
@@ -96,7 +98,9 @@ int agg_kv_compact_bytes(const agg_shape* shape, size_t* bytes, int64_t* M_pad);
 int64_t agg_kc_offset(int64_t m, int32_t d);
 int64_t agg_vc_offset(int64_t m, int32_t d);
 
-/* Host only.  Scratch bytes agg_kv_subsample needs (partial sums of the mean). */
+/* Host only.  Scratch bytes agg_kv_subsample needs: the partial sums from which the mean
+ * component of Sec. 4.3 (one mean key/value pair over all dropped patches) is formed in a fixed
+ * order. */
 size_t agg_workspace_bytes(const agg_shape* shape);
 
 /*

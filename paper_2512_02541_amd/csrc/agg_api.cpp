@@ -166,7 +166,8 @@ int agg_kv_subsample_static(const agg_shape* shape, const void* K, const void* V
   Geom g;
   int rc = make_geom(shape, &g, false);
   if (rc != AGG_OK) return rc;
-  if (!K || !V || !Kc || !Vc || !kmean || !vmean) return AGG_ERR_NULL;
+  if (!K || !V || !kmean || !vmean) return AGG_ERR_NULL;
+  if ((Kc == nullptr) != (Vc == nullptr)) return AGG_ERR_NULL;  // both or neither
   if (misaligned(K) || misaligned(V) || misaligned(Kc) || misaligned(Vc) || misaligned(kmean) ||
       misaligned(vmean) || ((uintptr_t)idx & 3u))
     return AGG_ERR_ALIGN;
