@@ -359,6 +359,42 @@ def test_idx_path_full_size():
 
 
 # ----------------------------------------------------------------------------
+# Key counts around the tile edges: the key loop walks 64-key tiles through three LDS buffers
+# (unrolled by three), masks the tail of the last tile only, and checks its row sums every 24
+# tiles.  One frame with strides (1,1) makes every token a key, so M = NQ can be set at will:
+# 1..8 tiles and two counts beyond the first sum check, each with a full, a one-key and a
+# 63-key last tile, through all three ways the kernel fetches its tiles.
+# ----------------------------------------------------------------------------
+TILE_EDGE_COUNTS = [64 * t + r for t in (0, 1, 2, 3, 4, 5, 6, 7, 24, 25) for r in (0, 1, 63)
+                    if 64 * t + r > 0]
+
+
+@pytest.mark.parametrize("nkeys", TILE_EDGE_COUNTS)
+def test_key_counts_around_tile_edges(nkeys):
+    H = 2
+    shape = agg.make_shape(1, 1, 1, nkeys, 0, H, 64, 1, 1, 1, flags=0)
+    assert shape.NQ == nkeys and agg.agg_kv_count(shape) == (nkeys, 0)
+    q, k, v = inputs.iid_qkv(1, nkeys, H, 64, seed=9000 + nkeys, device="cuda")
+    say("tile-edge case: %d keys = %d tiles, %d in the last" % (nkeys, (nkeys + 63) // 64,
+                                                               (nkeys - 1) % 64 + 1))
+    O, lse = harness.dense_forward(shape, q, k, v)          # rows of K/V in place
+    torch.cuda.synchronize()
+    rows = np.arange(nkeys, dtype=np.int64)
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    want_o, want_lse = orc.dense_rows(oshape(shape), qb, kb, vb, rows)
+    check_output(O, lse, want_o, want_lse, rows, "tile edge %d" % nkeys, q, k, shape.scale)
+    ref = harness.sga_forward(shape, q, k, v, poison=True)  # compacted copy
+    got = harness.alloc(shape, "cuda", poison=True)         # through the index list
+    agg.agg_kv_subsample(shape, k, v, None, None, got.idx, got.kmean, got.vmean, got.workspace,
+                         got.workspace.numel())
+    harness.attend_idx(got, q, k, v)
+    torch.cuda.synchronize()
+    for name, other in (("compacted", ref), ("index-driven", got)):
+        assert torch.equal(other.O.view(torch.int16), O.view(torch.int16)), (name, nkeys)
+        assert torch.equal(other.lse, lse), (name, nkeys)
+
+
+# ----------------------------------------------------------------------------
 # Frame attention (Global-to-Frame conversion of early global blocks)
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("case", [(2, 3, 5, 7, 2, 3), (1, 4, 16, 16, 5, 16), (1, 2, 37, 37, 5, 2)])
