@@ -394,6 +394,17 @@ def test_key_counts_around_tile_edges(nkeys):
         assert torch.equal(other.lse, lse), (name, nkeys)
 
 
+@pytest.mark.parametrize("nq", [1, 2, 31, 32, 33, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1025])
+def test_query_counts_around_tile_edges(nq):
+    """Query counts around the 32-query block, the 64-query wavefront and the 256-query
+    workgroup tile, with a subsampled key set (one frame, pi^3 rule, strides (1,3)) and both
+    extras: whole path against the oracle, then the index-driven path against the first."""
+    shape = agg.make_shape(1, 1, 1, nq, 0, 3, 64, 1, 3, 0)
+    q, k, v = inputs.iid_qkv(1, nq, 3, 64, seed=7000 + nq, device="cuda")
+    run_case(shape, q, k, v, what="query edge %d" % nq)
+    _idx_case(shape, q, k, v, "query edge %d" % nq)
+
+
 # ----------------------------------------------------------------------------
 # Frame attention (Global-to-Frame conversion of early global blocks)
 # ----------------------------------------------------------------------------
