@@ -65,7 +65,7 @@ typedef enum agg_status {
   AGG_OK = 0,
   AGG_ERR_NULL = -1,        /* a required pointer is NULL                          */
   AGG_ERR_SHAPE = -2,       /* a dimension or stride is < 1, or flags unknown      */
-  AGG_ERR_UNSUPPORTED = -3, /* D != 64                                             */
+  AGG_ERR_UNSUPPORTED = -3, /* D != 64; a block wider than 4096 channels           */
   AGG_ERR_ALIGN = -4,       /* a tensor pointer is not 16-byte aligned             */
   AGG_ERR_WORKSPACE = -5,   /* workspace smaller than the matching *_workspace_bytes */
   AGG_ERR_OVERFLOW = -6,    /* N*L, M_pad or a tensor's element count exceeds the index range */
@@ -190,6 +190,7 @@ int agg_frame_attn_fwd(const agg_shape* shape, const void* Q, const void* K, con
  * b_* (may be NULL), ln_gamma, ln_beta: float32 [C].  Q, K, V and the attention output
  * are bf16 tensors in the workspace, as in the calls above.  Rotary embeddings or
  * query/key normalisation, which the paper's text does not describe, are not applied.
+ * C may be at most 4096 (64 heads): wider blocks return AGG_ERR_UNSUPPORTED.
  */
 typedef struct agg_block_weights {
   const float* ln_gamma;

@@ -407,7 +407,7 @@ int agg_global_block_fwd(const agg_shape* shape, int mode, const agg_block_weigh
   if (!(w->ln_eps > 0.0f)) return AGG_ERR_SHAPE;
   if (workspace_bytes < p.total) return AGG_ERR_WORKSPACE;
   const int C = shape->H * kHeadDim;
-  if (C > 2048) return AGG_ERR_UNSUPPORTED;  // LayerNorm kernel: one wavefront per row
+  if (C > 4096) return AGG_ERR_UNSUPPORTED;  // LayerNorm kernel: a row lives in one wavefront's registers
   const int64_t rows = (int64_t)shape->B * shape->N * ((int64_t)shape->n_h * shape->n_w + shape->n_special);
   hipStream_t st = (hipStream_t)hip_stream;
   char* base = (char*)workspace;

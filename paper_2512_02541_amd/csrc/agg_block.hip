@@ -38,7 +38,7 @@ __device__ inline float hi16(uint32_t w) { return __uint_as_float(w & 0xFFFF0000
 // of 8; a lane owns 16-byte chunks lane, lane+64, ...
 // ---------------------------------------------------------------------------
 constexpr int kLnThreads = 256;
-constexpr int kLnMaxChunks = 4;  // per lane: supports C <= 64*8*4 = 2048
+constexpr int kLnMaxChunks = 8;  // per lane: supports C <= 64*8*8 = 4096
 
 __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* __restrict__ x,
                                                                const float* __restrict__ gamma,

@@ -405,6 +405,28 @@ def test_query_counts_around_tile_edges(nq):
     _idx_case(shape, q, k, v, "query edge %d" % nq)
 
 
+@pytest.mark.parametrize("H", [33, 40])
+def test_more_than_32_heads(H):
+    """Rows wider than 256 sixteen-byte chunks: the mean pass covers a row with two workgroups
+    side by side, the gather has a ragged last head group (33), and heads no longer divide
+    evenly over the XCD slots.  Whole path, index-driven path, dense baseline, frame attention."""
+    shape = agg.make_shape(1, 2, 6, 5, 1, H, 64, 2, 2, 1)
+    q, k, v = inputs.iid_qkv(1, shape.NQ, H, 64, seed=3300 + H, device="cuda")
+    run_case(shape, q, k, v, what="H=%d" % H)
+    _idx_case(shape, q, k, v, "H=%d" % H)
+    rows = np.arange(shape.NQ, dtype=np.int64)
+    qb, kb, vb = (inputs.bf16_bits(t) for t in (q, k, v))
+    O, lse = harness.dense_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    want_o, want_lse = orc.dense_rows(oshape(shape), qb, kb, vb, rows)
+    check_output(O, lse, want_o, want_lse, rows, "dense H=%d" % H, q, k, shape.scale)
+    O, lse = harness.frame_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    want_o, want_lse = orc.frame_rows(oshape(shape), qb, kb, vb, rows)
+    err = np.abs(O.float().cpu().numpy().astype(np.float64) - want_o)
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, (H, err.max(), err.mean())
+
+
 # ----------------------------------------------------------------------------
 # Frame attention (Global-to-Frame conversion of early global blocks)
 # ----------------------------------------------------------------------------
@@ -493,6 +515,27 @@ def test_global_block(mode):
 
 
 BLOCK_MAX, BLOCK_MEAN = 6e-2, 4e-3   # one block: see test_global_block
+
+
+def test_global_block_with_33_heads():
+    """A block whose width (2112) is not a multiple of the projection kernel's 256-column tile:
+    the last column tile of every projection is partial, and so is the last head group."""
+    from oracle import block_oracle as blk
+
+    shape = agg.make_shape(1, 2, 7, 6, 3, 33, 64, 2, 2, 1)
+    C = shape.H * 64
+    wts = inputs.block_weights(C, seed=777, device="cuda")
+    x = inputs.block_input(1, shape.NQ, C, seed=777, device="cuda")
+    y, _ = harness.block_forward(shape, agg.AGG_BLOCK_SGA, wts, x)
+    torch.cuda.synchronize()
+    host = {k: (v.double().cpu().numpy() if torch.is_tensor(v) else v) for k, v in wts.items()}
+    want = blk.block(oshape(shape), agg.AGG_BLOCK_SGA, inputs.bf16_bits(x), host)
+    got = y.double().cpu().numpy()
+    err = np.abs(got - want)
+    say("block with 33 heads: max %.3e mean %.3e" % (err.max(), err.mean()))
+    assert np.isfinite(got).all()
+    assert err.max() <= BLOCK_MAX and err.mean() <= BLOCK_MEAN, (err.max(), err.mean())
+
 
 
 def _host_weights(wts):

@@ -168,6 +168,9 @@ def test_error_paths_before_any_launch():
         assert blk(ctypes.byref(good), mode, None, fake, other, fake, bws, None) == -1
         assert blk(ctypes.byref(good), mode, ctypes.byref(w), fake, fake, fake, bws, None) == -2  # y aliases x
     assert agg.agg_block_workspace_bytes(good, 7) == 0
+    wide = agg.make_shape(1, 2, 16, 16, 5, 65, 64, 2, 2)    # 4160 channels: beyond the LayerNorm's row
+    assert blk(ctypes.byref(wide), agg.AGG_BLOCK_SGA, ctypes.byref(w), fake, ctypes.c_void_p(0x2000),
+               fake, 1 << 40, None) == -3
     assert blk(ctypes.byref(good), 7, ctypes.byref(w), fake, fake, fake, 1 << 40, None) == -2
 
     # caller-supplied lists
