@@ -746,6 +746,16 @@ def test_list_arbitrary_entries():
     assert (buf.n_dropped == 0).all()
 
 
+def test_list_path_with_33_heads():
+    """The list-driven pass where a row is wider than one workgroup's 256 chunks (the mean role
+    runs two workgroups side by side and only the first writes the run's count)."""
+    shape = agg.make_shape(2, 2, 6, 5, 3, 33, 64, 2, 2, 0)
+    q, k, v = inputs.iid_qkv(2, shape.NQ, 33, 64, seed=733, device="cuda")
+    rng = np.random.default_rng(33)
+    lists = np.stack([rng.choice(shape.NQ, 21, replace=False) for _ in range(2)]).astype(np.int32)
+    check_list_case(shape, torch.from_numpy(lists).cuda(), q, k, v, what="33 heads")
+
+
 def test_list_full_size_random_rule():
     """100 frames: one random token per window, sampled query rows against the oracle."""
     w = inputs.WORKLOADS["f100"]
@@ -825,7 +835,7 @@ def test_hip_graph_replays_of_block_and_list_paths():
 
 
 @pytest.mark.parametrize("case", [(2, 3, 7, 8, 5, 4, 3, 3, 1), (1, 2, 16, 16, 5, 16, 2, 2, 0),
-                                  (1, 3, 5, 7, 2, 3, 1, 2, 1)])
+                                  (1, 3, 5, 7, 2, 3, 1, 2, 1), (1, 2, 6, 5, 1, 33, 2, 2, 1)])
 def test_cell_mean_pooling(case):
     """agg_kv_pool: rows are window means (one bf16 rounding), and attention over them without
     extras matches plain attention over the oracle's pooled rows."""
