@@ -156,6 +156,8 @@ RAGGED = [
     (1, 4, 8, 8, 5, 16, 1, 2, 1),
     (1, 3, 6, 6, 5, 4, 7, 7, 0),     # strides larger than the grid: one patch per frame
     (1, 1, 6, 6, 5, 4, 2, 2, 1),     # single frame kept whole: nothing dropped
+    (1, 2, 4, 5, 70, 2, 2, 2, 1),    # more special tokens than a 64-row tile
+    (1, 2, 11, 4, 1, 2, 5, 1, 0),    # stride along the rows only
 ]
 
 
