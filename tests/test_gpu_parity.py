@@ -293,6 +293,19 @@ def test_full_size_workloads(name, part, parts):
     assert bool((o <= vmax + slack).all()) and bool((o >= vmin - slack).all())
 
 
+def test_mid_size_batch_of_three():
+    """Three scenes in one call (B = 3, 12 frames of the benchmark's 37 x 37 + 5 tokens, 16 heads,
+    pi^3 rule): every (batch, head) pair is its own key stream, numbered over the XCD slots;
+    distinct data per scene, 300 sampled rows against the oracle, then the index-driven path."""
+    shape = agg.make_shape(3, 12, 37, 37, 5, 16, 64, 2, 2, 0)
+    q, k, v = inputs.iid_qkv(3, shape.NQ, 16, 64, seed=31337, device="cuda")
+    rng = np.random.default_rng(12)
+    rows = np.unique(np.concatenate([rng.integers(0, shape.NQ, 290), [0, 255, 256, shape.NQ - 1]]))
+    mx, mn = run_case(shape, q, k, v, rows=rows.astype(np.int64), what="B=3")
+    say("B=3: %d rows, max-abs %.3e mean-abs %.3e" % (len(rows), mx, mn))
+    _idx_case(shape, q, k, v, "B=3")
+
+
 def test_full_size_dense_baseline():
     w = inputs.WORKLOADS["f100"]
     q, k, v = inputs.make_qkv(w, "cuda")
