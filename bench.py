@@ -233,6 +233,13 @@ def run_only(args, log):
                           "tflops_attn": fl / (ms * 1e-3) / 1e12,
                           "frac_peak": fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}))
         return 0
+    if args.only == "gather" and args.steps >= 5:
+        ms, mn = time_events(lambda: harness.subsample(buf, k, v), args.steps, 2)
+        nbytes = 2.0 * w.NQ * w.H * w.D * 2 + 2.0 * buf.M * w.H * w.D * 2
+        print(json.dumps({"only": "gather", "workload": args.workload, "launches": args.steps + 2,
+                          "ms_gather": ms, "ms_gather_min": mn,
+                          "gather_gbs": nbytes / (ms * 1e-3) / 1e9}))
+        return 0
     for i in range(args.steps):
         if args.only == "attn":
             harness.attend(buf, q, k, v)

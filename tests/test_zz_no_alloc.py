@@ -50,9 +50,9 @@ def test_static_scratch_matches_workspace_call_twice_in_a_row():
 
 
 def test_static_scratch_refuses_what_does_not_fit():
-    # 8 batch elements of 100 frames need 8 x 16 MiB of partial sums
-    w = inputs.WORKLOADS["f100"]
-    shape = agg.make_shape(8, w.N, w.n_h, w.n_w, w.n_special, w.H, w.D, w.s_h, w.s_w, 1, 3, None, 0.0)
+    # 3 batch elements of 800 frames need 3 x 15 MiB of partial sums
+    w = inputs.WORKLOADS["f800"]
+    shape = agg.make_shape(3, w.N, w.n_h, w.n_w, w.n_special, w.H, w.D, w.s_h, w.s_w, 1, 3, None, 0.0)
     assert agg.agg_workspace_bytes(shape) > agg.agg_static_scratch_bytes()
     dummy = torch.zeros(64, dtype=torch.float32, device="cuda")
     with pytest.raises(agg.AggError) as e:
