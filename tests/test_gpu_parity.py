@@ -795,6 +795,35 @@ def _capture(fn):
     return graph
 
 
+def test_hip_graph_of_static_subsample_and_index_driven_attention():
+    """The pair of calls a caller under graph capture would use: the subsample call whose scratch
+    lives inside the library (index list and mean terms only) and the attention that reads the
+    kept rows in place.  Each replay reproduces the eager result of the ordinary path."""
+    w = inputs.WORKLOADS["tiny"]
+    shape = harness.shape_of(w)
+    q, k, v = inputs.make_qkv(w, "cuda")
+    eager = harness.sga_forward(shape, q, k, v)
+    torch.cuda.synchronize()
+    buf = harness.alloc(shape, "cuda", poison=True)
+
+    def run():
+        agg.agg_kv_subsample_static(shape, k, v, None, None, buf.idx, buf.kmean, buf.vmean)
+        harness.attend_idx(buf, q, k, v)
+
+    graph = _capture(run)
+    for replay in range(3):
+        for t in (buf.O, buf.lse, buf.kmean, buf.vmean):
+            t.fill_(float("nan"))
+        buf.idx.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf.idx, eager.idx), replay
+        assert torch.equal(buf.kmean, eager.kmean) and torch.equal(buf.vmean, eager.vmean), replay
+        assert torch.equal(buf.O.view(torch.int16), eager.O.view(torch.int16)), replay
+        assert torch.equal(buf.lse, eager.lse), replay
+
+
 def test_hip_graph_replays_of_block_and_list_paths():
     """Every launch of the multi-kernel entry points is capturable (they clear with kernels,
     not memsets) and each replay reproduces the eager result bit for bit."""
