@@ -7,11 +7,16 @@
 // Mapping to gfx950
 //   * One workgroup = 4 wavefronts; a wavefront owns kQB blocks of 32 queries for the
 //     whole key loop and keeps Q and the output accumulator in registers.
-//   * The score tile is computed transposed, S^T = K * Q^T, with
-//     v_mfma_f32_32x32x16_bf16: a lane then holds 16 keys of ONE query, so row
-//     sums are in-register plus one exchange with lane^32, and the
-//     exponentiated tile is already in the B-operand layout of the second
-//     product O^T += V^T * P^T.  P never touches LDS.
+//   * Both products run on v_mfma_f32_16x16x32_bf16, which accumulates 32 products per pass
+//     through its four accumulator registers: half the accumulator traffic per flop of the
+//     32x32x16 shape, and the part is power-limited on this kernel (measured on hashed
+//     operands, MFMAs alone: 1.94 against 1.74 PFLOP/s).
+//   * The score tile is computed transposed, S^T = K * Q^T: a lane then holds keys of ONE
+//     query (four per 16-key tile), so row sums are in-register plus a reduction over the four
+//     lanes c, c+16, c+32, c+48, and the exponentiated tiles are already the B operand of the
+//     second product O^T += V^T * P^T.  P never touches LDS.  A 32-key block is scored as two
+//     16-key tiles whose rows are assigned to the block's keys such that the eight probabilities
+//     of a lane belong to exactly one 16-byte chunk of the compacted V tile (row_key below).
 //   * K/V arrive in "fragment order" (agg.h): a 64-key tile is a linear 8 KiB
 //     copy into LDS and every MFMA A operand is one conflict-free 16-byte read.
 //     Three tiles are resident: the one in use, the next one and the one being
@@ -35,14 +40,13 @@
 //     redo its rows in the general path (a second kernel behind this one, see
 //     the end of the file); ordinary attention logits never get there.  The
 //     sums are checked every few tiles, so an overflow ends the fast pass early.
-//   * General path: the same pipeline with a per-row reference, subtracted by the
-//     matrix core (a fifth, rank-2 product per unit adds minus the reference to
-//     the scores), so the vector ALU does no more per score than on the fast
-//     path.  The reference starts at the largest of the extras and the first 32
-//     keys and is raised lazily: a unit's row sums show when a score exceeds it
-//     by more than 2^100; only then (a rare, wavefront-uniform branch) is the
-//     unit's maximum taken, the accumulator rescaled and the unit redone.  No
-//     running maximum is computed otherwise.
+//   * General path: the same pipeline with a per-row reference.  The score MFMAs start from
+//     an accumulator holding minus the reference instead of zero, so the scores come out
+//     relative to it and the vector ALU does no more per score than on the fast path.  The
+//     reference starts at the largest of the extras and the first 32 keys and is raised
+//     lazily: a unit's row sums show when a score exceeds it by more than 2^100; only then
+//     (a rare, wavefront-uniform branch) is the unit's maximum taken, the accumulator
+//     rescaled and the unit redone.  No running maximum is computed otherwise.
 //   * The zero-padded rows of the last tile are masked there (the last tile is
 //     peeled), nowhere else.
 //   * The extras enter as the initial state (sum, accumulator) of either path, so
@@ -100,9 +104,9 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Lanes l and l ^ 32 hold the two halves of a query's keys.  v_permlane32_swap exchanges the
-// upper 32 lanes of its first operand with the lower 32 of its second; fed the same value twice
-// it returns (own, partner) in one order or the other, and both uses below are symmetric.
+// Exchange between lanes l and l ^ 32.  v_permlane32_swap exchanges the upper 32 lanes of its
+// first operand with the lower 32 of its second; fed the same value twice it returns
+// (own, partner) in one order or the other, and both uses below are symmetric.
 __device__ __forceinline__ float pair_max(float x) {
   const uint32_t b = __float_as_uint(x);
   const auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
@@ -143,43 +147,77 @@ __device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* q) {
 }
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 
-#define AGG_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a).h, (b).h, (c), 0, 0, 0)
+#define AGG_MFMA16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16((a).h, (b).h, (c), 0, 0, 0)
 
-// zero-padded rows of the last tile: key index inside the tile >= valid -> -inf
-__device__ __forceinline__ void mask16(f32x16& S, int kb, int valid, int g2) {
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int km = 32 * kb + 8 * (r >> 2) + 4 * g2 + (r & 3);
-    if (km >= valid) S[r] = -INFINITY;
-  }
+// Lane geometry of v_mfma_f32_16x16x32_bf16: c = lane & 15 is the row of the A operand, the
+// column of the B operand and of the result; G = lane >> 4 selects eight of the 32 contraction
+// elements (8 G .. 8 G + 7) in A and B, and result rows 4 G .. 4 G + 3.
+//
+// A 32-key block is scored as two 16-key tiles.  Tile kt takes the block's keys
+//     row i  ->  key (i & 7) + 16 (i >> 3) + 8 kt          (tile 0: 0-7, 16-23; tile 1: 8-15, 24-31)
+// so that the eight probabilities a lane holds after both tiles (rows 4 G .. 4 G + 3 of each) are
+// exactly the eight keys of ONE 16-byte chunk of the compacted V tile (agg.h: chunk (t, g) holds
+// keys 16 t + 4 g + {0..3, 8..11}; here t = 2 kb + (G >> 1), g = G & 1): the exponentiated scores
+// are the B operand of O^T += V^T P^T as they stand, and V fragments are plain 16-byte reads.
+__device__ __forceinline__ int row_key(int i) { return (i & 7) + 16 * (i >> 3); }
+
+// sum / maximum over the four lanes c, c + 16, c + 32, c + 48 that share a query
+__device__ __forceinline__ float quad_sum(float x) {
+  x += __shfl_xor(x, 16);
+  return pair_sum(x);
+}
+__device__ __forceinline__ float quad_max(float x) {
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return pair_max(x);
 }
 
-// probabilities of 16 base-2 logits, packed for the PV MFMA, and their sum (two chains)
-__device__ __forceinline__ void exp16(const f32x16& S, Frag (&P)[2], float& l0, float& l1) {
+// zero-padded rows of the last tile: key index inside the tile >= valid -> -inf
+__device__ __forceinline__ void mask_unit(f32x4 (&S)[4], int kb, int valid, int G) {
 #pragma unroll
-  for (int hf = 0; hf < 2; ++hf)
+  for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float e0 = fast_exp2(S[hf * 8 + 2 * i]);
-      const float e1 = fast_exp2(S[hf * 8 + 2 * i + 1]);
-      P[hf].u[i] = pack_bf16(e0, e1);
-      l0 += e0;
-      l1 += e1;
+    for (int r = 0; r < 4; ++r) {
+      const int km = 32 * kb + 8 * kt + row_key(4 * G + r);
+      if (km >= valid) {
+        S[2 * kt][r] = -INFINITY;
+        S[2 * kt + 1][r] = -INFINITY;
+      }
     }
 }
 
-// Everything a wavefront keeps in registers across the key loop.
+// Everything a wavefront keeps in registers across the key loop.  qb = 32-query block, j = its
+// 16-query tile, kt = 16-key tile of a key block, h = half of the channel range, dt = 16-channel
+// tile of the output.
 struct Wave {
-  Frag Qf[kQB][4];     // B operand of S^T = K Q^T, pre-multiplied by scale*log2(e)
-  f32x16 O[kQB][2];    // O^T accumulator; channel = 32 db + 8 (r/4) + 4 g2 + r%4
-  f32x16 S[kQB];       // score tiles in flight
-  float la[kQB][2];    // two partial row sums per query block
-  float mref[kQB];     // general path: the row's reference (base-2 logit)
-  Frag mneg[kQB];      // general path: minus that reference as a B operand (see set_reference)
-  Frag a[4];           // K fragments of the 32-key block whose scores are being computed
-  Frag v[4];           // V fragments of the block whose P V is being accumulated; hf*2 + db
-  Frag P[2];           // probabilities of the previous unit
+  Frag Qf[kQB][4];      // [qb][2 j + h]: B operand of S^T = K Q^T, pre-multiplied by scale*log2(e)
+  f32x4 O[kQB][2][4];   // [qb][j][dt]: O^T accumulator; channel = 16 dt + 4 G + r, query = c
+  f32x4 S[kQB][4];      // [qb][2 kt + j]: score tiles in flight; key = row_key(4 G + r) + 8 kt
+  float la[kQB][2];     // [qb][j]: this lane's part of the row sum
+  float mref[kQB][2];   // general path: the row's reference (base-2 logit)
+  Frag a[4];            // [2 kt + h]: K fragments of the block whose scores are being computed
+  Frag v[4];            // [dt]: V fragments of the block whose P V is being accumulated
+  Frag P[2];            // [j]: probabilities of the previous unit
 };
+
+// probabilities of the 8 base-2 logits a lane holds for the queries of tile j, packed as the B
+// operand of the PV MFMA (contraction elements 8 G .. 8 G + 7: tile 0's rows, then tile 1's),
+// and their sum
+__device__ __forceinline__ void exp_unit(const f32x4 (&S)[4], Frag (&P)[2], float& l0, float& l1) {
+  // the two query tiles alternate, so that consecutive additions go to different sums
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        float& l = j ? l1 : l0;
+        const float e0 = fast_exp2(S[2 * kt + j][2 * i]);
+        const float e1 = fast_exp2(S[2 * kt + j][2 * i + 1]);
+        P[j].u[2 * kt + i] = pack_bf16(e0, e1);
+        l += e0;
+        l += e1;
+      }
+}
 
 // Where the key/value tiles come from.
 //   kSrcCompact: the fragment-order compacted tensors of agg_kv_subsample: a tile is a linear
@@ -199,31 +237,45 @@ enum { kSrcCompact = 0, kSrcRows = 1, kSrcIndexed = 2 };
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) char lds_char;
 
+// chunk swizzle of a K row in the row modes: the 16 rows a lane group reads (i, i + 16 for eight
+// consecutive i) must fall on 16 different 16-byte slots of the 256-byte bank period
+__device__ __forceinline__ uint32_t k_swizzle(uint32_t row) {
+  return ((row >> 1) & 3u) | (((row >> 4) & 1u) << 2);
+}
+
 // per-lane LDS byte offsets of the fragment reads (row modes) or chunk numbers (compact mode)
 struct FragAddr {
-  int lane, vlane;       // compact: chunk numbers inside a K / V tile
-  uint32_t k[4];         // rows: K fragment of channel step ks (chunk swizzle depends on the lane)
-  uint32_t v[2];         // rows: V fragment of channel block db
+  int lane;
+  int kc[2];             // compact: chunk of tile kt inside a (key block, channel half) run
+  int vc;                // compact: chunk inside a key block's V run (plus 16 dt)
+  uint32_t k[4];         // rows: K fragment [2 kt + h]
+  uint32_t v[4];         // rows: V fragment of channel tile dt (first four keys; +8 rows: the others)
 };
 
 __device__ __forceinline__ FragAddr frag_addr(int lane) {
   FragAddr f;
-  const int l32 = lane & 31, g2 = lane >> 5;
+  const int c = lane & 15, G = lane >> 4;
   f.lane = lane;
-  f.vlane = g2 * 64 + l32;
-  // K, row l32 of a 32-key block: chunk (2 ks + g2) ^ ((row >> 1) & 7), row parity picks the
-  // half of the 256-byte bank period
+  // compact K tile in LDS: [kb][h][G][32 keys], a key at position (key with bits 3 and 4
+  // exchanged): tile kt's sixteen keys are then consecutive
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks)
-    f.k[ks] = (uint32_t)(l32 * 128 + (((2 * ks + g2) ^ ((l32 >> 1) & 7)) * 16));
-  // V: lane i of a 16-lane group reads row 4 g2 + i/4 (+ the block's first row), the 8 bytes at
-  // channel 32 db + 16 (group & 1) + 4 (i % 4); chunk bit 2 is flipped on rows 2, 3 mod 4
-  const int i = lane & 15, grp = (lane >> 4) & 1;
-  const int row = 4 * g2 + (i >> 2);
+  for (int kt = 0; kt < 2; ++kt) f.kc[kt] = G * 32 + 16 * kt + c;
+  f.vc = G * 64 + c;
 #pragma unroll
-  for (int db = 0; db < 2; ++db) {
-    const int chunk = (4 * db + 2 * grp + ((i & 3) >> 1)) ^ (4 * ((row >> 1) & 1));
-    f.v[db] = (uint32_t)(row * 128 + chunk * 16 + (i & 1) * 8);
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t row = (uint32_t)(row_key(c) + 8 * kt);
+      f.k[2 * kt + h] = row * 128u + (((uint32_t)(4 * h + G) ^ k_swizzle(row)) * 16u);
+    }
+  // V: the lanes 4 i' .. 4 i' + 3 of a 16-lane group point at row i' of the group's first four
+  // keys (16 (G >> 1) + 4 (G & 1) + i'), each at 8 of the 32 bytes of channels 16 dt .. 16 dt + 15;
+  // chunk bit 2 is flipped on rows 2, 3 mod 4
+  const int row = 16 * (G >> 1) + 4 * (G & 1) + (c >> 2);
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) {
+    const int chunk = (2 * dt + ((c & 3) >> 1)) ^ (4 * ((row >> 1) & 1));
+    f.v[dt] = (uint32_t)(row * 128 + chunk * 16 + (c & 1) * 8);
   }
   return f;
 }
@@ -233,12 +285,15 @@ __device__ __forceinline__ void load_k_frags(const u32x4* __restrict__ lds, int 
                                              const FragAddr& f, Frag (&a)[4]) {
   if (kSrc == kSrcCompact) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) a[ks].u = lds[buf * kChunks + (kb * 4 + ks) * 64 + f.lane];
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        a[2 * kt + h].u = lds[buf * kChunks + kb * 256 + h * 128 + f.kc[kt]];
   } else {
     const lds_char* base = (const lds_char*)lds + buf * (kChunks * 16) + kb * (32 * 128);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-      a[ks].u = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(base + f.k[ks]);
+    for (int i = 0; i < 4; ++i)
+      a[i].u = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(base + f.k[i]);
   }
 }
 template <int kSrc>
@@ -246,26 +301,22 @@ __device__ __forceinline__ void load_v_frags(const u32x4* __restrict__ lds, int 
                                              const FragAddr& f, Frag (&v)[4]) {
   if (kSrc == kSrcCompact) {
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-      for (int db = 0; db < 2; ++db)
-        v[hf * 2 + db].u =
-            lds[(kLdsTiles + buf) * kChunks + (kb * 2 + hf) * 128 + db * 32 + f.vlane];
+    for (int dt = 0; dt < 4; ++dt)
+      v[dt].u = lds[(kLdsTiles + buf) * kChunks + kb * 256 + dt * 16 + f.vc];
   } else {
     lds_char* base = (lds_char*)lds + (kLdsTiles + buf) * (kChunks * 16) + kb * (32 * 128);
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-      for (int db = 0; db < 2; ++db) {
-        // keys 16 hf + 4 g2 + 0..3, then 16 hf + 8 + 4 g2 + 0..3: the order the P operand has
-        lds_char* at = base + hf * (16 * 128) + f.v[db];
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)at);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(at + 8 * 128));
-        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-        v[hf * 2 + db].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
-      }
+    for (int dt = 0; dt < 4; ++dt) {
+      // the group's first four keys, then the four that lie eight rows further on: the order
+      // the P operand has
+      lds_char* at = base + f.v[dt];
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)at);
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(at + 8 * 128));
+      const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+      v[dt].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
+    }
   }
 }
 
@@ -304,10 +355,14 @@ struct TileCopier {
       const uint32_t slot = (uint32_t)tid + hh * kAttnThreads;  // 0 .. 511
       row[hh] = slot >> 3;
       const uint32_t c = slot & 7;
-      const uint32_t ck = (c ^ ((row[hh] >> 1) & 7)) * 16u;
+      const uint32_t ck = (c ^ k_swizzle(row[hh])) * 16u;
       const uint32_t cv = (c ^ (4u * ((row[hh] >> 1) & 1))) * 16u;
       if (kSrc == kSrcCompact) {
-        vk[hh] = vv[hh] = slot * 16u;
+        // K: the LDS slot of a key has bits 3 and 4 of the key number exchanged (frag_addr)
+        const uint32_t key = slot & 31u;
+        const uint32_t swapped = (key & 7u) | ((key & 8u) << 1) | ((key & 16u) >> 1);
+        vk[hh] = ((slot & ~31u) | swapped) * 16u;
+        vv[hh] = slot * 16u;
       } else if (kSrc == kSrcRows) {
         vk[hh] = row[hh] * s.row_bytes + ck;
         vv[hh] = row[hh] * s.row_bytes + cv;
@@ -373,28 +428,40 @@ struct TileCopier {
   }
 };
 
-// General path: the row reference is subtracted by the matrix core.  A fifth product per unit
-// adds  ones(32 keys x 16) * R(16 x 32 queries)  to the scores, where column q of R holds
-// -(m_hi, m_lo, 0, ...) and m_hi + m_lo -- two bf16 values -- IS the reference: the reference is
-// whatever that sum comes to (exactly representable in float), so nothing is lost by the split.
-__device__ __forceinline__ void set_reference(Wave& w, int qb, float m, int g2) {
-  const float hi = bf16_lo(pack_bf16(m, 0.f));
-  const float lo = bf16_lo(pack_bf16(m - hi, 0.f));
-  w.mref[qb] = hi + lo;
-  w.mneg[qb].u = u32x4{g2 == 0 ? pack_bf16(-hi, -lo) : 0u, 0u, 0u, 0u};
+// Scores of one unit: the 32 keys of block fragments `a` against the 32 queries of block tq.
+// General path: the accumulator starts at minus the row's reference instead of zero, so the
+// scores come out relative to it at no cost (the reference is a float, nothing is split).
+template <bool kGen>
+__device__ __forceinline__ void score_unit(const Wave& w, int tq, f32x4 (&Sn)[4]) {
+  f32x4 init[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const float m = kGen ? -w.mref[tq][j] : 0.f;
+    init[j] = f32x4{m, m, m, m};
+  }
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) Sn[2 * kt + j] = AGG_MFMA16(w.a[2 * kt], w.Qf[tq][2 * j], init[j]);
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      Sn[2 * kt + j] = AGG_MFMA16(w.a[2 * kt + 1], w.Qf[tq][2 * j + 1], Sn[2 * kt + j]);
 }
-__device__ __forceinline__ Frag ones_frag(int g2) {
-  Frag f;
-  f.u = u32x4{g2 == 0 ? 0x3F803F80u : 0u, 0u, 0u, 0u};  // bf16 (1, 1) in contraction slots 0, 1
-  return f;
+// O^T += V^T P^T for the unit whose probabilities are in w.P
+__device__ __forceinline__ void pv_unit(Wave& w, int pq) {
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) w.O[pq][j][dt] = AGG_MFMA16(w.v[dt], w.P[j], w.O[pq][j][dt]);
 }
 
 // One step of the pipeline inside tile `cur` (see the file header).  kLast: the tile is the
 // last one (`valid` of its 64 rows exist, nothing follows).  kGen: general path.
 template <int kSrc, bool kLast, bool kGen>
 __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ lds, int cur, int nxt,
-                                           int valid, const FragAddr& fa, int g2) {
-  const int lane = fa.lane;
+                                           int valid, const FragAddr& fa, int G) {
 #pragma unroll
   for (int sg = 0; sg < 2 * kQB; ++sg) {
     const int kb = sg / kQB, qb = sg % kQB;
@@ -405,19 +472,8 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
 
     // ---- matrix core, part 1: scores of unit `un` ----
     const bool do_qk = !(kLast && beyond);
-    f32x16 Sn;
-    if (do_qk) {
-      f32x16 z;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) z[r] = 0.f;
-      if (kGen) {  // scores relative to the row's reference
-        const Frag one = ones_frag(g2);
-        z = AGG_MFMA(one, w.mneg[tq], z);
-      }
-      Sn = AGG_MFMA(w.a[0], w.Qf[tq][0], z);
-#pragma unroll
-      for (int ks = 1; ks < 4; ++ks) Sn = AGG_MFMA(w.a[ks], w.Qf[tq][ks], Sn);
-    }
+    f32x4 Sn[4];
+    if (do_qk) score_unit<kGen>(w, tq, Sn);
     if (tq == kQB - 1) {  // that was the block's last unit: fragments of the following block
       if (un / kQB == 0) load_k_frags<kSrc>(lds, cur, 1, fa, w.a);
       else if (!kLast) load_k_frags<kSrc>(lds, nxt, 0, fa, w.a);
@@ -427,33 +483,32 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
     Frag Pn[2];
     float u0 = 0.f, u1 = 0.f;  // general path: the unit's own row sums
     {
-      f32x16& S = w.S[qb];
-      if (kLast && valid < kTileRows) mask16(S, kb, valid, g2);
+      f32x4 (&S)[4] = w.S[qb];
+      if (kLast && valid < kTileRows) mask_unit(S, kb, valid, G);
       if (!kGen) {
-        exp16(S, Pn, w.la[qb][0], w.la[qb][1]);
+        exp_unit(S, Pn, w.la[qb][0], w.la[qb][1]);
       } else {
         // the scores are already relative to the row's reference; whether it still holds is
         // looked at below, behind the step's last MFMA
-        exp16(S, Pn, u0, u1);
+        exp_unit(S, Pn, u0, u1);
       }
     }
-    if (do_qk) w.S[tq] = Sn;
+    if (do_qk) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w.S[tq][i] = Sn[i];
+    }
 
     // ---- matrix core, part 2: P V of unit sg - 1 ----
-    w.O[pq][0] = AGG_MFMA(w.v[0], w.P[0], w.O[pq][0]);
-    w.O[pq][1] = AGG_MFMA(w.v[1], w.P[0], w.O[pq][1]);
-    w.O[pq][0] = AGG_MFMA(w.v[2], w.P[1], w.O[pq][0]);
-    w.O[pq][1] = AGG_MFMA(w.v[3], w.P[1], w.O[pq][1]);
+    pv_unit(w, pq);
     if (qb == 0) load_v_frags<kSrc>(lds, cur, kb, fa, w.v);  // the previous block is done with them
     w.P[0] = Pn[0];
     w.P[1] = Pn[1];
-    // Issue order inside the step: one MFMA, then its share of the vector work (two
+    // Issue order inside the step: two MFMAs, then their share of the vector work (two
     // exponentials, one conversion, two additions).  Left to itself the scheduler bunches the
     // MFMAs, and the wavefront then stalls on the matrix pipe with vector work still to issue.
-    if (kGen) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // the reference product
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // two MFMAs (they share their A operand)
       __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);  // transcendental
       __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // other vector ALU
     }
@@ -464,26 +519,32 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
       // it (the others keep theirs: shift 0, factor 1), scale what they have accumulated, and
       // redo the unit's probabilities (its scores are untouched until the next step).
       if (__builtin_amdgcn_ballot_w64(!(u0 + u1 < kUnitHi)) != 0) {
-        f32x16& S = w.S[qb];
-        float mx = S[0];
+        f32x4 (&S)[4] = w.S[qb];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[r]);
-        mx = pair_max(mx);  // both lanes of a row agree
-        const float old = w.mref[qb];
-        if (mx > kLazy) set_reference(w, qb, old + mx, g2);
-        const float d = w.mref[qb] - old;
-        const float f = fast_exp2(-d);
+        for (int j = 0; j < 2; ++j) {
+          float mx = S[j][0];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          S[r] -= d;
-          w.O[qb][0][r] *= f;
-          w.O[qb][1][r] *= f;
+          for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mx = fmaxf(mx, S[2 * kt + j][r]);
+          mx = quad_max(mx);  // the four lanes of a row agree
+          const float old = w.mref[qb][j];
+          if (mx > kLazy) w.mref[qb][j] = old + mx;
+          const float d = w.mref[qb][j] - old;
+          const float f = fast_exp2(-d);
+#pragma unroll
+          for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[2 * kt + j][r] -= d;
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) w.O[qb][j][dt][r] *= f;
+          w.la[qb][j] *= f;
         }
-        w.la[qb][0] *= f;
-        w.la[qb][1] *= f;
         u0 = 0.f;
         u1 = 0.f;
-        exp16(S, w.P, u0, u1);
+        exp_unit(S, w.P, u0, u1);
       }
       w.la[qb][0] += u0;
       w.la[qb][1] += u1;
@@ -497,7 +558,7 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
 template <int kSrc, bool kGen, class FirstTile>
 __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const KvSource& src,
                                          int ntiles, int last_valid, int tid, int wave,
-                                         const FragAddr& fa, int g2, FirstTile&& first_tile) {
+                                         const FragAddr& fa, int G, FirstTile&& first_tile) {
   TileCopier<kSrc> copy;
   copy.init(src, lds, tid, wave);
   copy.issue(0);
@@ -513,18 +574,7 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
   w.P[0].u = u32x4{0u, 0u, 0u, 0u};
   w.P[1].u = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-  for (int qb = 0; qb + 1 < kQB; ++qb) {
-    f32x16 s;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
-    if (kGen) {
-      const Frag one = ones_frag(g2);
-      s = AGG_MFMA(one, w.mneg[qb], s);
-    }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) s = AGG_MFMA(w.a[ks], w.Qf[qb][ks], s);
-    w.S[qb] = s;
-  }
+  for (int qb = 0; qb + 1 < kQB; ++qb) score_unit<kGen>(w, qb, w.S[qb]);
 
   int t = 0, cur = 0;
   bool ok = true;
@@ -536,7 +586,7 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
     break;                                                                                  \
   }                                                                                         \
   if (t + 2 < ntiles) copy.issue((CUR + 2) % kLdsTiles);                                    \
-  tile_steps<kSrc, false, kGen>(w, lds, CUR, (CUR + 1) % kLdsTiles, kTileRows, fa, g2);     \
+  tile_steps<kSrc, false, kGen>(w, lds, CUR, (CUR + 1) % kLdsTiles, kTileRows, fa, G);      \
   wait_vm0();                                                                               \
   lds_barrier();                                                                            \
   ++t;
@@ -557,11 +607,8 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
   }
   if (!ok) return false;
   // last tile (runtime buffer number), then the P V of its last unit
-  tile_steps<kSrc, true, kGen>(w, lds, cur, 0, last_valid, fa, g2);
-  w.O[kQB - 1][0] = AGG_MFMA(w.v[0], w.P[0], w.O[kQB - 1][0]);
-  w.O[kQB - 1][1] = AGG_MFMA(w.v[1], w.P[0], w.O[kQB - 1][1]);
-  w.O[kQB - 1][0] = AGG_MFMA(w.v[2], w.P[1], w.O[kQB - 1][0]);
-  w.O[kQB - 1][1] = AGG_MFMA(w.v[3], w.P[1], w.O[kQB - 1][1]);
+  tile_steps<kSrc, true, kGen>(w, lds, cur, 0, last_valid, fa, G);
+  pv_unit(w, kQB - 1);
   return true;
 }
 
@@ -592,8 +639,8 @@ __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int l32 = lane & 31;
-  const int g2 = lane >> 5;
+  const int c = lane & 15;
+  const int G = lane >> 4;
   const FragAddr fa = frag_addr(lane);
 
   const int ntiles = (int)(g.M_pad / kTileRows);
@@ -615,98 +662,107 @@ __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) 
   }
 
   Wave w;
-  bool dropped[kQB];
-  float l_self[kQB], l_mean[kQB];  // base-2 logits of the extras (-inf when absent)
+  bool dropped[kQB][2];
+  float l_self[kQB][2], l_mean[kQB][2];  // base-2 logits of the extras (-inf when absent)
   // caller's list: membership comes from a bitmap, the dropped count from device memory
   const int64_t n_drop = p.nd_dev ? (int64_t)p.nd_dev[b] : g.n_dropped;
   const bool use_mean = (p.flags & AGG_MEAN) && n_drop > 0;
   const bool use_diag = (p.flags & AGG_DIAG) && (p.kept_bits != nullptr || n_drop > 0);
   const uint32_t* kbits = p.kept_bits ? p.kept_bits + (int64_t)b * ((g.NQ + 31) / 32) : nullptr;
   const int64_t q_wave = (int64_t)qt * kQTile + wave * kWaveQ;
+  // first element of query (qb, j, c)'s row of this head in Q, K, V and O
+  auto row_base = [&](int qb, int j) {
+    const int64_t q = q_wave + qb * 32 + j * 16 + c;
+    const int64_t qc = q < g.NQ ? q : g.NQ - 1;  // tail rows recompute the last query, never stored
+    return (((int64_t)b * g.NQ + qc) * g.H + h) * kHeadDim;
+  };
 
   // ---- Q fragments and the logits of the extras ----
+  // a lane holds channels 32 h + 8 G .. + 7 (h = 0, 1) of its query: the four lanes c + 16 G
+  // share the channel range
 #pragma unroll
-  for (int qb = 0; qb < kQB; ++qb) {
-    const int64_t q = q_wave + qb * 32 + l32;
-    const int64_t qc = q < g.NQ ? q : g.NQ - 1;  // tail rows recompute the last query, never stored
-    const int64_t qbase = (((int64_t)b * g.NQ + qc) * g.H + h) * kHeadDim;
+  for (int qb = 0; qb < kQB; ++qb)
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      u32x4 raw = *reinterpret_cast<const u32x4*>(p.Q + qbase + ks * 16 + g2 * 8);
+    for (int j = 0; j < 2; ++j) {
+      const int64_t q = q_wave + qb * 32 + j * 16 + c;
+      const int64_t qbase = row_base(qb, j);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        w.Qf[qb][ks].u[i] = pack_bf16(bf16_lo(raw[i]) * p.qscale, bf16_hi(raw[i]) * p.qscale);
-    }
-    // lanes l and l^32 hold the two halves of the channel range
-    dropped[qb] = use_diag && q < g.NQ &&
-                  (kbits ? ((kbits[q >> 5] >> (q & 31)) & 1u) == 0u : (bool)token_is_dropped(g, q));
-    float dot_self = 0.f, dot_mean = 0.f;
-    if (use_mean || use_diag) {
-      const float* km = p.kmean + ((int64_t)b * g.H + h) * kHeadDim;
+      for (int hh = 0; hh < 2; ++hh) {
+        u32x4 raw = *reinterpret_cast<const u32x4*>(p.Q + qbase + hh * 32 + G * 8);
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const int d0 = ks * 16 + g2 * 8;
-        float qv[8];
+        for (int i = 0; i < 4; ++i)
+          w.Qf[qb][2 * j + hh].u[i] =
+              pack_bf16(bf16_lo(raw[i]) * p.qscale, bf16_hi(raw[i]) * p.qscale);
+      }
+      dropped[qb][j] =
+          use_diag && q < g.NQ &&
+          (kbits ? ((kbits[q >> 5] >> (q & 31)) & 1u) == 0u : (bool)token_is_dropped(g, q));
+      float dot_self = 0.f, dot_mean = 0.f;
+      if (use_mean || use_diag) {
+        const float* km = p.kmean + ((int64_t)b * g.H + h) * kHeadDim;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          qv[2 * i] = bf16_lo(w.Qf[qb][ks].u[i]);
-          qv[2 * i + 1] = bf16_hi(w.Qf[qb][ks].u[i]);
-        }
-        if (use_mean) {
-          f32x4 c0 = *reinterpret_cast<const f32x4*>(km + d0);
-          f32x4 c1 = *reinterpret_cast<const f32x4*>(km + d0 + 4);
+        for (int hh = 0; hh < 2; ++hh) {
+          const int d0 = hh * 32 + G * 8;
+          float qv[8];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) dot_mean += qv[i] * c0[i] + qv[4 + i] * c1[i];
-        }
-        if (dropped[qb]) {
-          u32x4 kr = *reinterpret_cast<const u32x4*>(p.K + qbase + d0);
+          for (int i = 0; i < 4; ++i) {
+            qv[2 * i] = bf16_lo(w.Qf[qb][2 * j + hh].u[i]);
+            qv[2 * i + 1] = bf16_hi(w.Qf[qb][2 * j + hh].u[i]);
+          }
+          if (use_mean) {
+            f32x4 c0 = *reinterpret_cast<const f32x4*>(km + d0);
+            f32x4 c1 = *reinterpret_cast<const f32x4*>(km + d0 + 4);
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            dot_self += qv[2 * i] * bf16_lo(kr[i]) + qv[2 * i + 1] * bf16_hi(kr[i]);
+            for (int i = 0; i < 4; ++i) dot_mean += qv[i] * c0[i] + qv[4 + i] * c1[i];
+          }
+          if (dropped[qb][j]) {
+            u32x4 kr = *reinterpret_cast<const u32x4*>(p.K + qbase + d0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              dot_self += qv[2 * i] * bf16_lo(kr[i]) + qv[2 * i + 1] * bf16_hi(kr[i]);
+          }
         }
       }
+      dot_self = quad_sum(dot_self);
+      dot_mean = quad_sum(dot_mean);
+      l_self[qb][j] = dropped[qb][j] ? dot_self : -INFINITY;
+      l_mean[qb][j] = use_mean ? dot_mean + p.mean_bias2 : -INFINITY;
     }
-    dot_self = pair_sum(dot_self);
-    dot_mean = pair_sum(dot_mean);
-    l_self[qb] = dropped[qb] ? dot_self : -INFINITY;
-    l_mean[qb] = use_mean ? dot_mean + p.mean_bias2 : -INFINITY;
-  }
 
   // Initial state = extras weighted by exp2(logit - m0):  O0[d] = w_self v_i[d] + w_mean vmean[d]
-  auto init_extras = [&](int qb, float m0) {
-    const float w_self = dropped[qb] ? fast_exp2(l_self[qb] - m0) : 0.f;
-    const float w_mean = use_mean ? fast_exp2(l_mean[qb] - m0) : 0.f;
-    w.la[qb][0] = (g2 == 0) ? (w_self + w_mean) : 0.f;  // lanes l and l^32 split a row's sum
-    w.la[qb][1] = 0.f;
-    const int64_t q = q_wave + qb * 32 + l32;
-    const int64_t qc = q < g.NQ ? q : g.NQ - 1;
-    const int64_t qbase = (((int64_t)b * g.NQ + qc) * g.H + h) * kHeadDim;
+  auto init_extras = [&](int qb, int j, float m0) {
+    const float w_self = dropped[qb][j] ? fast_exp2(l_self[qb][j] - m0) : 0.f;
+    const float w_mean = use_mean ? fast_exp2(l_mean[qb][j] - m0) : 0.f;
+    w.la[qb][j] = (G == 0) ? (w_self + w_mean) : 0.f;  // four lanes split a row's sum
+    const int64_t qbase = row_base(qb, j);
     const float* vm = p.vmean + ((int64_t)b * g.H + h) * kHeadDim;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int d0 = 32 * db + 8 * r4 + 4 * g2;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        if (use_mean) {
-          f32x4 mv = *reinterpret_cast<const f32x4*>(vm + d0);
-          acc = mv * w_mean;
-        }
-        if (dropped[qb]) {
-          u32x2 vr = *reinterpret_cast<const u32x2*>(p.V + qbase + d0);
-          acc[0] += w_self * bf16_lo(vr[0]);
-          acc[1] += w_self * bf16_hi(vr[0]);
-          acc[2] += w_self * bf16_lo(vr[1]);
-          acc[3] += w_self * bf16_hi(vr[1]);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) w.O[qb][db][r4 * 4 + i] = acc[i];
+    for (int dt = 0; dt < 4; ++dt) {
+      const int d0 = 16 * dt + 4 * G;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      if (use_mean) {
+        f32x4 mv = *reinterpret_cast<const f32x4*>(vm + d0);
+        acc = mv * w_mean;
       }
+      if (dropped[qb][j]) {
+        u32x2 vr = *reinterpret_cast<const u32x2*>(p.V + qbase + d0);
+        acc[0] += w_self * bf16_lo(vr[0]);
+        acc[1] += w_self * bf16_hi(vr[0]);
+        acc[2] += w_self * bf16_lo(vr[1]);
+        acc[3] += w_self * bf16_hi(vr[1]);
+      }
+      w.O[qb][j][dt] = acc;
+    }
   };
 
   if (!kGen) {
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) init_extras(qb, 0.f);
+    for (int qb = 0; qb < kQB; ++qb)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        w.mref[qb][j] = 0.f;
+        init_extras(qb, j, 0.f);
+      }
   }
   // general path: the reference is the largest of the extras and of the first 32 keys (row 0
   // always exists); taken when the first tile's K fragments are in registers
@@ -715,64 +771,71 @@ __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) 
     const int valid0 = ntiles == 1 ? last_valid : kTileRows;
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb) {
-      f32x16 s;
+      w.mref[qb][0] = 0.f;
+      w.mref[qb][1] = 0.f;
+      f32x4 s[4];
+      score_unit<kGen>(w, qb, s);
+      if (valid0 < 32) mask_unit(s, 0, valid0, G);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+      for (int j = 0; j < 2; ++j) {
+        float mx = s[j][0];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) s = AGG_MFMA(w.a[ks], w.Qf[qb][ks], s);
-      if (valid0 < 32) mask16(s, 0, valid0, g2);
-      float mx = s[0];
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-      mx = pair_max(mx);
-      mx = fmaxf(mx, fmaxf(l_self[qb], l_mean[qb]));
-      // a NaN or infinite score cannot serve as reference; the row's result is NaN anyway
-      if (!(fabsf(mx) < 3.0e38f)) mx = 0.f;
-      set_reference(w, qb, mx, g2);
-      init_extras(qb, w.mref[qb]);
+          for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[2 * kt + j][r]);
+        mx = quad_max(mx);
+        mx = fmaxf(mx, fmaxf(l_self[qb][j], l_mean[qb][j]));
+        // a NaN or infinite score cannot serve as reference; the row's result is NaN anyway
+        if (!(fabsf(mx) < 3.0e38f)) mx = 0.f;
+        w.mref[qb][j] = mx;
+        init_extras(qb, j, mx);
+      }
     }
   };
 
-  const bool done = key_loop<kSrc, kGen>(w, lds, src, ntiles, last_valid, tid, wave, fa, g2,
+  const bool done = key_loop<kSrc, kGen>(w, lds, src, ntiles, last_valid, tid, wave, fa, G,
                                          first_tile);
-  float l_fin[kQB];
+  float l_fin[kQB][2];
   bool unsafe = false;
 #pragma unroll
-  for (int qb = 0; qb < kQB; ++qb) {
-    l_fin[qb] = pair_sum(w.la[qb][0] + w.la[qb][1]);
-    // a sum outside [2^-90, 2^90] (or NaN): the unreferenced exponentials were not safe
-    unsafe = unsafe || !(l_fin[qb] < kSumHi) || !(l_fin[qb] > kSumLo);
-  }
+  for (int qb = 0; qb < kQB; ++qb)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      l_fin[qb][j] = quad_sum(w.la[qb][j]);
+      // a sum outside [2^-90, 2^90] (or NaN): the unreferenced exponentials were not safe
+      unsafe = unsafe || !(l_fin[qb][j] < kSumHi) || !(l_fin[qb][j] > kSumLo);
+    }
   if (!kGen) {
     if (!done) return false;  // uniform: decided by a workgroup-wide vote inside the loop
     if (__syncthreads_or(unsafe ? 1 : 0)) return false;
   }
 
   // ---- normalise and store ----
-  // A lane holds four consecutive channels of one query per register group: stored from there,
-  // every instruction would scatter 8-byte pieces over 32 rows that lie 2*H*64 bytes apart.
+  // A lane holds four consecutive channels of one query per accumulator tile: stored from there,
+  // every instruction would scatter 8-byte pieces over 16 rows that lie 2*H*64 bytes apart.
   // Each wavefront instead turns its tile, 32 queries at a time, through a private part of the
   // (now idle) K/V LDS and writes whole 128-byte (query, head) rows, eight per instruction.
   __syncthreads();  // every wavefront is done with the K/V tiles
   uint16_t* epi = smem + wave * (32 * kEpiStride);
 #pragma unroll
   for (int qb = 0; qb < kQB; ++qb) {
-    const float l = l_fin[qb];
-    const float inv = 1.0f / l;
-#pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int d0 = 32 * db + 8 * r4 + 4 * g2;
-        u32x2 o2;
-        o2[0] = pack_bf16(w.O[qb][db][r4 * 4 + 0] * inv, w.O[qb][db][r4 * 4 + 1] * inv);
-        o2[1] = pack_bf16(w.O[qb][db][r4 * 4 + 2] * inv, w.O[qb][db][r4 * 4 + 3] * inv);
-        *reinterpret_cast<u32x2*>(epi + l32 * kEpiStride + d0) = o2;
-      }
     const int64_t q0 = q_wave + qb * 32;
-    if (p.lse && g2 == 0 && q0 + l32 < g.NQ)
-      p.lse[((int64_t)b * g.H + h) * g.NQ + q0 + l32] =
-          ((kGen ? w.mref[qb] : 0.f) + log2f(l)) * kLn2;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float l = l_fin[qb][j];
+      const float inv = 1.0f / l;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        const int d0 = 16 * dt + 4 * G;
+        u32x2 o2;
+        o2[0] = pack_bf16(w.O[qb][j][dt][0] * inv, w.O[qb][j][dt][1] * inv);
+        o2[1] = pack_bf16(w.O[qb][j][dt][2] * inv, w.O[qb][j][dt][3] * inv);
+        *reinterpret_cast<u32x2*>(epi + (16 * j + c) * kEpiStride + d0) = o2;
+      }
+      if (p.lse && G == 0 && q0 + 16 * j + c < g.NQ)
+        p.lse[((int64_t)b * g.H + h) * g.NQ + q0 + 16 * j + c] =
+            ((kGen ? w.mref[qb][j] : 0.f) + log2f(l)) * kLn2;
+    }
     // the wavefront's own writes, read back by other lanes of the same wavefront
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
     __builtin_amdgcn_wave_barrier();
