@@ -17,6 +17,10 @@
 //     second product O^T += V^T * P^T.  P never touches LDS.  A 32-key block is scored as two
 //     16-key tiles whose rows are assigned to the block's keys such that the eight probabilities
 //     of a lane belong to exactly one 16-byte chunk of the compacted V tile (row_key below).
+//     On the fast path the row sums are a ninth product of the same shape per query tile, a
+//     row of ones against P^T (+12.5 % MFMAs): the vector ALU, which has to issue twice as
+//     many MFMAs as with the larger shape, then does nothing per score but exponentiate and
+//     convert, and every lane ends up with its query's whole sum.
 //   * K/V arrive in "fragment order" (agg.h): a 64-key tile is a linear 8 KiB
 //     copy into LDS and every MFMA A operand is one conflict-free 16-byte read.
 //     Three tiles are resident: the one in use, the next one and the one being
@@ -35,7 +39,7 @@
 //   * Fast path: Q is pre-multiplied by scale*log2(e) and the probabilities are
 //     exp2 of the raw base-2 logits, with NO reference subtracted: softmax is
 //     invariant to the reference, float/bf16 exponents cover 2^+-126, and the
-//     per-score work shrinks to exp + convert + add.  A row whose sum leaves
+//     per-score work shrinks to exp + convert.  A row whose sum leaves
 //     [2^-90, 2^90] (logits beyond about +-60 nats) makes the whole workgroup
 //     redo its rows in the general path (a second kernel behind this one, see
 //     the end of the file); ordinary attention logits never get there.  The
@@ -192,18 +196,31 @@ struct Wave {
   Frag Qf[kQB][4];      // [qb][2 j + h]: B operand of S^T = K Q^T, pre-multiplied by scale*log2(e)
   f32x4 O[kQB][2][4];   // [qb][j][dt]: O^T accumulator; channel = 16 dt + 4 G + r, query = c
   f32x4 S[kQB][4];      // [qb][2 kt + j]: score tiles in flight; key = row_key(4 G + r) + 8 kt
-  float la[kQB][2];     // [qb][j]: this lane's part of the row sum
+  f32x4 L[kQB][2];      // [qb][j]: fast path: the whole row sum, kept by the matrix core (four equal copies)
+  float la[kQB][2];     // [qb][j]: general path: this lane's part of the row sum
   float mref[kQB][2];   // general path: the row's reference (base-2 logit)
   Frag a[4];            // [2 kt + h]: K fragments of the block whose scores are being computed
   Frag v[4];            // [dt]: V fragments of the block whose P V is being accumulated
   Frag P[2];            // [j]: probabilities of the previous unit
 };
 
-// probabilities of the 8 base-2 logits a lane holds for the queries of tile j, packed as the B
-// operand of the PV MFMA (contraction elements 8 G .. 8 G + 7: tile 0's rows, then tile 1's),
-// and their sum
-__device__ __forceinline__ void exp_unit(const f32x4 (&S)[4], Frag (&P)[2], float& l0, float& l1) {
-  // the two query tiles alternate, so that consecutive additions go to different sums
+// Probabilities of the 16 base-2 logits a lane holds for a unit, packed as the B operands of
+// the PV MFMAs: for query tile j, contraction elements 8 G .. 8 G + 7 are key tile 0's rows, then
+// key tile 1's.  The two query tiles alternate in the instruction stream.
+__device__ __forceinline__ void exp_unit(const f32x4 (&S)[4], Frag (&P)[2]) {
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        P[j].u[2 * kt + i] = pack_bf16(fast_exp2(S[2 * kt + j][2 * i]), fast_exp2(S[2 * kt + j][2 * i + 1]));
+}
+
+// General path: the same, and the sums of each query tile's part (there the vector ALU keeps
+// the sums: the unit's own sum is what tells that a score has run away from the row's reference,
+// and it is needed before the probabilities reach the matrix core)
+__device__ __forceinline__ void exp_unit_sum(const f32x4 (&S)[4], Frag (&P)[2], float& l0, float& l1) {
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -449,12 +466,22 @@ __device__ __forceinline__ void score_unit(const Wave& w, int tq, f32x4 (&Sn)[4]
     for (int j = 0; j < 2; ++j)
       Sn[2 * kt + j] = AGG_MFMA16(w.a[2 * kt + 1], w.Qf[tq][2 * j + 1], Sn[2 * kt + j]);
 }
-// O^T += V^T P^T for the unit whose probabilities are in w.P
+// O^T += V^T P^T for the unit whose probabilities are in w.P.  Fast path: the row sums are one
+// more product, a row of ones against P^T: every row of that 16 x 16 result is the sum of the
+// unit's 32 probabilities of a query, so each lane keeps the whole sum and the vector ALU adds
+// nothing.
+template <bool kGen>
 __device__ __forceinline__ void pv_unit(Wave& w, int pq) {
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int j = 0; j < 2; ++j) w.O[pq][j][dt] = AGG_MFMA16(w.v[dt], w.P[j], w.O[pq][j][dt]);
+  if (!kGen) {
+    Frag ones;
+    ones.u = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+#pragma unroll
+    for (int j = 0; j < 2; ++j) w.L[pq][j] = AGG_MFMA16(ones, w.P[j], w.L[pq][j]);
+  }
 }
 
 // One step of the pipeline inside tile `cur` (see the file header).  kLast: the tile is the
@@ -486,11 +513,11 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
       f32x4 (&S)[4] = w.S[qb];
       if (kLast && valid < kTileRows) mask_unit(S, kb, valid, G);
       if (!kGen) {
-        exp_unit(S, Pn, w.la[qb][0], w.la[qb][1]);
+        exp_unit(S, Pn);
       } else {
         // the scores are already relative to the row's reference; whether it still holds is
         // looked at below, behind the step's last MFMA
-        exp_unit(S, Pn, u0, u1);
+        exp_unit_sum(S, Pn, u0, u1);
       }
     }
     if (do_qk) {
@@ -499,18 +526,31 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
     }
 
     // ---- matrix core, part 2: P V of unit sg - 1 ----
-    pv_unit(w, pq);
+    pv_unit<kGen>(w, pq);
     if (qb == 0) load_v_frags<kSrc>(lds, cur, kb, fa, w.v);  // the previous block is done with them
     w.P[0] = Pn[0];
     w.P[1] = Pn[1];
-    // Issue order inside the step: two MFMAs, then their share of the vector work (two
-    // exponentials, one conversion, two additions).  Left to itself the scheduler bunches the
-    // MFMAs, and the wavefront then stalls on the matrix pipe with vector work still to issue.
+    // Issue order inside the step: MFMAs and exponentials alternate one by one, a conversion
+    // after every second pair (general path: pairs of MFMAs, then their share of the vector work,
+    // which there includes the additions).  Left to itself the scheduler bunches the MFMAs, and
+    // the wavefront then stalls on the matrix pipe with vector work still to issue.
+    if (!kGen) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // the row-sum products of the last unit
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // two MFMAs (they share their A operand)
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);  // transcendental
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // other vector ALU
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);  // transcendental
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);  // the pair's conversion
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // conversion and two additions
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
     if (kGen) {
@@ -544,7 +584,7 @@ __device__ __forceinline__ void tile_steps(Wave& w, const u32x4* __restrict__ ld
         }
         u0 = 0.f;
         u1 = 0.f;
-        exp_unit(S, w.P, u0, u1);
+        exp_unit_sum(S, w.P, u0, u1);
       }
       w.la[qb][0] += u0;
       w.la[qb][1] += u1;
@@ -598,7 +638,7 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
       bool bad = false;
 #pragma unroll
       for (int qb = 0; qb < kQB; ++qb)
-        bad = bad || !(w.la[qb][0] < kSumHi) || !(w.la[qb][1] < kSumHi);
+        bad = bad || !(w.L[qb][0][0] < kSumHi) || !(w.L[qb][1][0] < kSumHi);
       if (__syncthreads_or(bad ? 1 : 0)) {
         ok = false;
         break;
@@ -608,7 +648,7 @@ __device__ __forceinline__ bool key_loop(Wave& w, u32x4* __restrict__ lds, const
   if (!ok) return false;
   // last tile (runtime buffer number), then the P V of its last unit
   tile_steps<kSrc, true, kGen>(w, lds, cur, 0, last_valid, fa, G);
-  pv_unit(w, kQB - 1);
+  pv_unit<kGen>(w, kQB - 1);
   return true;
 }
 
@@ -733,7 +773,9 @@ __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) 
   auto init_extras = [&](int qb, int j, float m0) {
     const float w_self = dropped[qb][j] ? fast_exp2(l_self[qb][j] - m0) : 0.f;
     const float w_mean = use_mean ? fast_exp2(l_mean[qb][j] - m0) : 0.f;
-    w.la[qb][j] = (G == 0) ? (w_self + w_mean) : 0.f;  // four lanes split a row's sum
+    const float l0 = w_self + w_mean;
+    if (kGen) w.la[qb][j] = (G == 0) ? l0 : 0.f;  // four lanes split a row's sum
+    else w.L[qb][j] = f32x4{l0, l0, l0, l0};      // every lane keeps the whole sum
     const int64_t qbase = row_base(qb, j);
     const float* vm = p.vmean + ((int64_t)b * g.H + h) * kHeadDim;
 #pragma unroll
@@ -801,7 +843,7 @@ __device__ __forceinline__ bool attend(const AttnArgs& p, int b, int h, int qt) 
   for (int qb = 0; qb < kQB; ++qb)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      l_fin[qb][j] = quad_sum(w.la[qb][j]);
+      l_fin[qb][j] = kGen ? quad_sum(w.la[qb][j]) : w.L[qb][j][0];
       // a sum outside [2^-90, 2^90] (or NaN): the unreferenced exponentials were not safe
       unsafe = unsafe || !(l_fin[qb][j] < kSumHi) || !(l_fin[qb][j] > kSumLo);
     }
