@@ -40,6 +40,9 @@ __device__ inline float hi16(uint32_t w) { return __uint_as_float(w & 0xFFFF0000
 constexpr int kLnThreads = 256;
 constexpr int kLnMaxChunks = 8;  // per lane: supports C <= 64*8*8 = 4096
 
+// kChunks = 16-byte chunks per lane (4 up to 2048 channels, else 8): the row lives in registers,
+// and the narrower instance keeps enough wavefronts resident to run at the memory rate
+template <int kChunks>
 __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* __restrict__ x,
                                                                const float* __restrict__ gamma,
                                                                const float* __restrict__ beta,
@@ -50,10 +53,10 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
   if (row >= rows) return;
   const int nchunk = C / 8;
   const uint16_t* xr = x + row * C;
-  float v[kLnMaxChunks][8];
+  float v[kChunks][8];
   float sum = 0.f;
 #pragma unroll
-  for (int c = 0; c < kLnMaxChunks; ++c) {
+  for (int c = 0; c < kChunks; ++c) {
     const int ch = lane + 64 * c;
     if (ch < nchunk) {
       u32x4 raw = *reinterpret_cast<const u32x4*>(xr + ch * 8);
@@ -70,7 +73,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
   const float mean = sum / (float)C;
   float sq = 0.f;
 #pragma unroll
-  for (int c = 0; c < kLnMaxChunks; ++c) {
+  for (int c = 0; c < kChunks; ++c) {
     const int ch = lane + 64 * c;
     if (ch < nchunk) {
 #pragma unroll
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
   const float rstd = rsqrtf(sq / (float)C + eps);
   uint16_t* yr = y + row * C;
 #pragma unroll
-  for (int c = 0; c < kLnMaxChunks; ++c) {
+  for (int c = 0; c < kChunks; ++c) {
     const int ch = lane + 64 * c;
     if (ch < nchunk) {
       float o[8];
@@ -286,8 +289,12 @@ hipError_t launch_layernorm(const void* x, const float* gamma, const float* beta
   const int64_t groups = (rows + (kLnThreads / 64) - 1) / (kLnThreads / 64);
   if (groups > 0x7FFFFFFF) return hipErrorInvalidConfiguration;
   (void)hipGetLastError();
-  hipLaunchKernelGGL(layernorm_kernel, dim3((unsigned)groups), dim3(kLnThreads), 0, st,
-                     (const uint16_t*)x, gamma, beta, (uint16_t*)y, rows, C, eps);
+  if (C <= 64 * 8 * 4)
+    hipLaunchKernelGGL(layernorm_kernel<4>, dim3((unsigned)groups), dim3(kLnThreads), 0, st,
+                       (const uint16_t*)x, gamma, beta, (uint16_t*)y, rows, C, eps);
+  else
+    hipLaunchKernelGGL(layernorm_kernel<kLnMaxChunks>, dim3((unsigned)groups), dim3(kLnThreads), 0,
+                       st, (const uint16_t*)x, gamma, beta, (uint16_t*)y, rows, C, eps);
   return hipGetLastError();
 }
 
