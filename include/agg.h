@@ -28,8 +28,10 @@
  * Compacted key/value format ("fragment order")
  *   Kc and Vc hold, per (batch, head), the M kept rows padded with zero rows to
  *   M_pad = 64*ceil(M/64), as consecutive 64-row tiles of 4096 bf16 (8 KiB).
- *   Inside a tile the elements are permuted so that a linear copy into LDS lets
- *   every wavefront lane fetch its MFMA operand as one 16-byte read:
+ *   Inside a tile the elements are grouped in 16-byte chunks (eight channels of
+ *   one key for Kc, eight keys of one channel for Vc) such that a copy into LDS
+ *   chunk by chunk lets every wavefront lane fetch its MFMA operand as one
+ *   16-byte read:
  *     Kc: row m, channel d  ->  tile m/64, then with km = m%64
  *         ((( (km/32)*4 + d/16 )*2 + (d%16)/8 )*32 + km%32)*8 + d%8
  *     Vc: row m, channel d  ->  tile m/64, then with km = m%64, u = km%16
